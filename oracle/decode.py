@@ -1,0 +1,207 @@
+"""Oracle decoding loops.  TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+  stepwise     greedy stepwise decoding in semi-autoregressive block order: one
+               token per model forward, the most confident masked position of
+               the current block (Section 3.1; Figure 2 caption).  This is the
+               result every other routine must reproduce.
+  ssd          Self Speculative Decoding, greedy chain tree (Section 3.2,
+               Algorithm 1): self-draft, select, build N+1 nodes, verify them
+               in one batched forward, accept the longest matching prefix plus
+               the last valid node's own prediction, reuse that node's
+               predictions as the next drafts.
+  bruteforce   stepwise decoding with no cache: the whole sequence is
+               recomputed under the block-causal mask for every token.
+
+Readings where the paper is silent (all also applied by the HIP path):
+  * confidence c = softmax probability of the arg-max token (Section 3.2.2);
+  * the mask token can never be predicted (excluded from max / arg-max / sum);
+  * ties: lowest token id; lowest position;
+  * a draft matches only if position AND token equal the stepwise choice
+    (Section 5.1: a different generation order is a failure);
+  * drafts come from the current block only, and at most (#masked - 1) of them,
+    so the leaf node always has a position left to predict; with zero drafts the
+    verification forward is a plain stepwise step (Algorithm 1's fallback);
+  * next drafts are read off the last valid node's own outputs, no extra
+    forward (Section 3.2.4, "without duplicate context").
+"""
+from __future__ import annotations
+
+import math
+
+import torch
+
+from .model import KVCache, forward_full_blockcausal, forward_segment
+
+
+# --------------------------------------------------------------------------
+# per-node prediction and the two selection rules
+# --------------------------------------------------------------------------
+def predict(logits, mask_id):
+    """Per row: arg-max token t (mask id excluded, ties -> lowest id), max
+    logit m, confidence c = exp(m) / sum_v exp(logit_v) = 1 / sum_v exp(logit_v - m),
+    and the top-1 minus top-2 logit margin (used only by the parity protocol)."""
+    l = logits.clone()
+    l[:, mask_id] = float("-inf")
+    V = l.shape[1]
+    m = l.max(dim=-1).values
+    ids = torch.arange(V)
+    t = torch.where(l == m[:, None], ids[None, :], torch.full((1, V), V)).min(dim=-1).values
+    c = 1.0 / torch.exp(l - m[:, None]).sum(dim=-1)
+    l2 = l.clone()
+    l2[torch.arange(l.shape[0]), t] = float("-inf")
+    margin = m - l2.max(dim=-1).values
+    return t, m, c, margin
+
+
+def stepwise_choice(c, masked):
+    """Position of the highest confidence among masked positions (ties -> lowest)."""
+    best = None
+    for p, is_masked in enumerate(masked):
+        if is_masked and (best is None or c[p] > c[best]):
+            best = p
+    return best
+
+
+def rank_positions(c, masked, exclude=None):
+    """Masked positions ordered by confidence, high to low (ties -> lowest position)."""
+    ps = [p for p, mk in enumerate(masked) if mk and p != exclude]
+    return sorted(ps, key=lambda p: (-float(c[p]), p))
+
+
+def build_chain(tok, masked, drafts):
+    """Greedy chain of len(drafts)+1 nodes (Section 3.2.3): node i is the current
+    block state with drafts 1..i written in."""
+    nodes = []
+    t, mk = list(tok), list(masked)
+    nodes.append((list(t), list(mk)))
+    for (q, d) in drafts:
+        assert mk[q], "a draft position must still be masked"
+        t[q], mk[q] = d, False
+        nodes.append((list(t), list(mk)))
+    return nodes
+
+
+def accept_chain(node_t, node_c, node_masked, drafts, n_draft_next):
+    """Chain traversal (Section 3.2.4).  node_t[i][p], node_c[i][p]: prediction and
+    confidence of node i at position p; node_masked[i][p]: masked in node i.
+    Returns (accepted [(pos, tok)], next_drafts [(pos, tok)], m = #matched drafts).
+
+    Node m's stepwise choice is compared with draft m+1; the walk stops at the
+    first mismatch; the accepted tokens are the m matched drafts plus node m's
+    own choice, so between 1 and len(drafts)+1 tokens."""
+    m = 0
+    while True:
+        p = stepwise_choice(node_c[m], node_masked[m])
+        t = int(node_t[m][p])
+        if m < len(drafts) and (p, t) == (drafts[m][0], int(drafts[m][1])):
+            m += 1
+            continue
+        break
+    accepted = [(q, int(d)) for (q, d) in drafts[:m]] + [(p, t)]
+    rest = rank_positions(node_c[m], node_masked[m], exclude=p)
+    n_next = min(n_draft_next, max(len(rest) - 1, 0))
+    next_drafts = [(q, int(node_t[m][q])) for q in rest[:n_next]]
+    return accepted, next_drafts, m
+
+
+# --------------------------------------------------------------------------
+# decoding loops
+# --------------------------------------------------------------------------
+def _blocks(gen_len, block):
+    return [(j * block, min(block, gen_len - j * block)) for j in range(math.ceil(gen_len / block))]
+
+
+def _prefill(w, cfg, prompt, dtype):
+    cache = KVCache(cfg["n_layers"])
+    _, kv = forward_segment(w, cfg, prompt, 0, cache, dtype, need_logits=False)
+    cache.append(kv)
+    return cache
+
+
+def _node_forward(w, cfg, tok, S, cache, dtype):
+    logits, _ = forward_segment(w, cfg, tok, S, cache, dtype)
+    return predict(logits, cfg["mask_id"])
+
+
+def stepwise(w, cfg, prompt, gen_len, block, dtype=torch.float64, trace=None, max_blocks=None):
+    """Greedy stepwise decoding.  Returns (tokens, stats)."""
+    P = len(prompt)
+    cache = _prefill(w, cfg, prompt, dtype)
+    out, forwards, kv_passes = [], 0, 1
+    for bi, (off, Bj) in enumerate(_blocks(gen_len, block)):
+        if max_blocks is not None and bi >= max_blocks:
+            break
+        S = P + off
+        tok, masked = [cfg["mask_id"]] * Bj, [True] * Bj
+        while any(masked):
+            t, m, c, margin = _node_forward(w, cfg, tok, S, cache, dtype)
+            forwards += 1
+            p = stepwise_choice(c, masked)
+            if trace is not None:
+                trace.append(dict(S=S, tok=list(tok), masked=list(masked), drafts=[],
+                                  t=[t], m=[m], c=[c], margin=[margin],
+                                  accepted=[(p, int(t[p]))], next_drafts=[]))
+            tok[p], masked[p] = int(t[p]), False
+        _, kv = forward_segment(w, cfg, tok, S, cache, dtype, need_logits=False)
+        cache.append(kv)
+        kv_passes += 1
+        out += tok
+    return out, dict(forwards=forwards, kv_passes=kv_passes)
+
+
+def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None, max_blocks=None):
+    """Self Speculative Decoding with draft length n_draft (Algorithm 1).
+    Returns (tokens, stats) with stats['accept_hist'][a] = number of forwards
+    that accepted a tokens."""
+    P = len(prompt)
+    cache = _prefill(w, cfg, prompt, dtype)
+    out, forwards, kv_passes = [], 0, 1
+    hist = [0] * (n_draft + 2)
+    for bi, (off, Bj) in enumerate(_blocks(gen_len, block)):
+        if max_blocks is not None and bi >= max_blocks:
+            break
+        S = P + off
+        tok, masked = [cfg["mask_id"]] * Bj, [True] * Bj
+        drafts = []            # the block-start self-draft is a chain with no drafts
+        while any(masked):
+            nodes = build_chain(tok, masked, drafts)
+            # one batched forward over all nodes (Eq. 5); nodes do not see each other
+            preds = [_node_forward(w, cfg, nt, S, cache, dtype) for (nt, _) in nodes]
+            forwards += 1
+            accepted, next_drafts, m = accept_chain(
+                [p[0] for p in preds], [p[2] for p in preds], [nm for (_, nm) in nodes],
+                drafts, n_draft)
+            if trace is not None:
+                trace.append(dict(S=S, tok=list(tok), masked=list(masked), drafts=list(drafts),
+                                  t=[p[0] for p in preds], m=[p[1] for p in preds],
+                                  c=[p[2] for p in preds], margin=[p[3] for p in preds],
+                                  accepted=list(accepted), next_drafts=list(next_drafts)))
+            hist[len(accepted)] += 1
+            for (q, d) in accepted:
+                assert masked[q]
+                tok[q], masked[q] = d, False
+            drafts = next_drafts
+        _, kv = forward_segment(w, cfg, tok, S, cache, dtype, need_logits=False)
+        cache.append(kv)
+        kv_passes += 1
+        out += tok
+    return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
+
+
+def bruteforce(w, cfg, prompt, gen_len, block, dtype=torch.float64):
+    """Stepwise decoding with no cache: one token per forward, every forward
+    recomputes the whole sequence (prompt + all blocks) under the block-causal
+    mask."""
+    P = len(prompt)
+    x = list(prompt) + [cfg["mask_id"]] * gen_len
+    seg = [0] * P + [1 + i // block for i in range(gen_len)]
+    forwards = 0
+    for (off, Bj) in _blocks(gen_len, block):
+        masked = [True] * Bj
+        while any(masked):
+            logits = forward_full_blockcausal(w, cfg, x, seg, dtype)
+            forwards += 1
+            t, m, c, _ = predict(logits[P + off: P + off + Bj], cfg["mask_id"])
+            p = stepwise_choice(c, masked)
+            x[P + off + p], masked[p] = int(t[p]), False
+    return x[P:], dict(forwards=forwards)

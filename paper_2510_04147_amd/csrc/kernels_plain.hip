@@ -1,0 +1,541 @@
+// Plain (FMA, no matrix cores) kernels for every step of the forward, for fp32
+// and bf16 storage.  They are the complete path for fp32 models and the
+// fallback / cross-check for bf16.  Every reduction runs in a fixed order that
+// depends only on the reduced extent, never on how many rows a launch holds,
+// so a row's result is bit-identical whether it is computed in a 1-node or an
+// (N+1)-node forward: that is what makes the batched verification (Eq. 5)
+// reproduce stepwise decoding exactly.
+#include "ssd_internal.h"
+
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float ld_f(const float* p) { return *p; }
+__device__ __forceinline__ float ld_f(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+    uint32_t x = __float_as_uint(f);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x40);   // NaN stays NaN
+    x += 0x7fffu + ((x >> 16) & 1u);                                            // round to nearest even
+    return (uint16_t)(x >> 16);
+}
+__device__ __forceinline__ void st_f(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_f(bf16_t* p, float v) { *p = f2bf(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------------
+// a0: tree build.  One work-group per node: node j of a decode group is the
+// block state with drafts 1..j written in (Section 3.2.3).
+// ------------------------------------------------------------------------
+__global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
+                             const int* __restrict__ raw_tok, int* __restrict__ row_tok,
+                             int* __restrict__ row_pos, int* __restrict__ row_node,
+                             int* __restrict__ out_tok, int mask_id, int max_seq_len) {
+    const int ni = blockIdx.x;
+    if (ni >= fw->n_nodes) return;
+    const NodeDesc nd = fw->nodes[ni];
+    const GroupDesc g = fw->groups[nd.group];
+    SeqState* s = &state[nd.seq];
+    for (int p = threadIdx.x; p < nd.blen; p += blockDim.x) {
+        int tok;
+        if (g.mode == GM_RAW) {
+            tok = raw_tok[g.raw_off + p];
+        } else if (g.mode == GM_APPEND) {
+            tok = s->tok[p];
+            if (g.out_off >= 0) out_tok[(size_t)nd.seq * max_seq_len + g.out_off + p] = tok;
+        } else if (g.fresh) {
+            tok = mask_id;
+        } else {
+            tok = s->tok[p];
+            for (int j = 0; j < nd.j; ++j)
+                if (s->draft_pos[j] == p) tok = s->draft_tok[j];
+        }
+        const int row = nd.row0 + p;
+        row_tok[row] = tok;
+        row_pos[row] = nd.S + p;
+        row_node[row] = ni;
+    }
+    if (g.mode == GM_DECODE && g.fresh && nd.j == 0) {
+        // a fresh block: every position masked, no drafts (Algorithm 1, line 3)
+        for (int p = threadIdx.x; p < SSD_MAX_BLOCK; p += blockDim.x) s->tok[p] = mask_id;
+        if (threadIdx.x == 0) {
+            s->masked = nd.blen >= 64 ? ~0ull : ((1ull << nd.blen) - 1ull);
+            s->n_draft = 0;
+        }
+    }
+}
+
+// a1: embedding gather into the fp32 residual stream.
+template <typename T>
+__global__ void k_embed(const T* __restrict__ embed, const int* __restrict__ row_tok, float* __restrict__ h, int d) {
+    const int row = blockIdx.x;
+    const T* e = embed + (size_t)row_tok[row] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)row * d + i] = ld_f(e + i);
+}
+
+// a2/a6/a9: h += sum of split-K partial sums (fixed order), then RMSNorm.
+template <typename T>
+__global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float* __restrict__ part, int n_part,
+                                              size_t part_stride, const float* __restrict__ gain,
+                                              T* __restrict__ xn, int d, float eps) {
+    const int row = blockIdx.x;
+    float* hr = h + (size_t)row * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = hr[i];
+        for (int s = 0; s < n_part; ++s) v += part[s * part_stride + (size_t)row * d + i];
+        if (n_part) hr[i] = v;
+        ss += v * v;
+    }
+    __shared__ float red[4];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    const float r = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256) st_f(xn + (size_t)row * d + i, hr[i] * r * gain[i]);
+}
+
+// Rotary embedding (rotate-half pairing) of Q and K from the fp32 projections,
+// conversion to the operand type, and the cache write for nodes that own
+// finished tokens.
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ qkv,
+                                              const int* __restrict__ row_pos, const int* __restrict__ row_node,
+                                              const float* __restrict__ cosT, const float* __restrict__ sinT,
+                                              T* __restrict__ q, T* __restrict__ k, T* __restrict__ v,
+                                              T* __restrict__ kcache, T* __restrict__ vcache, int Hq, int Hkv,
+                                              int dh, int layer, int max_seqs, int max_seq_len) {
+    const int row = blockIdx.x;
+    const int pos = row_pos[row];
+    const NodeDesc nd = fw->nodes[row_node[row]];
+    const int half = dh >> 1;
+    const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
+    const float* src = qkv + (size_t)row * nqkv;
+    const size_t cbase = (((size_t)layer * max_seqs + nd.seq) * Hkv) * (size_t)max_seq_len * dh;
+    for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += 256) {
+        const int head = idx / half, i = idx - head * half;
+        const float x1 = src[head * dh + i], x2 = src[head * dh + i + half];
+        const float c = cosT[(size_t)pos * half + i], s = sinT[(size_t)pos * half + i];
+        const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
+        if (head < Hq) {
+            st_f(q + (size_t)row * nq + head * dh + i, o1);
+            st_f(q + (size_t)row * nq + head * dh + i + half, o2);
+        } else {
+            const int kh = head - Hq;
+            st_f(k + (size_t)row * nkv + kh * dh + i, o1);
+            st_f(k + (size_t)row * nkv + kh * dh + i + half, o2);
+            if (nd.write_kv) {
+                T* dst = kcache + cbase + ((size_t)kh * max_seq_len + pos) * dh;
+                st_f(dst + i, o1);
+                st_f(dst + i + half, o2);
+            }
+        }
+    }
+    for (int idx = threadIdx.x; idx < nkv; idx += 256) {
+        const float x = src[nq + nkv + idx];
+        st_f(v + (size_t)row * nkv + idx, x);
+        if (nd.write_kv) {
+            const int kh = idx / dh, i = idx - kh * dh;
+            st_f(vcache + cbase + ((size_t)kh * max_seq_len + pos) * dh + i, x);
+        }
+    }
+}
+
+// a4 (plain): one wave per (row, query head).  Keys = the sequence's cached
+// prefix [0,S) followed by the node's own rows; online softmax in fp32 over
+// key tiles of 64 in position order.
+template <typename T>
+__global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__ fw, const int* __restrict__ row_node,
+                                                   const T* __restrict__ q, const T* __restrict__ k,
+                                                   const T* __restrict__ v, const T* __restrict__ kcache,
+                                                   const T* __restrict__ vcache, T* __restrict__ out, int Hq,
+                                                   int Hkv, int dh, int layer, int max_seqs, int max_seq_len) {
+    const int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const NodeDesc nd = fw->nodes[row_node[row]];
+    const int kvh = head / (Hq / Hkv);
+    const int nq = Hq * dh, nkv = Hkv * dh;
+    __shared__ float qs[128];
+    for (int i = lane; i < dh; i += 64) qs[i] = ld_f(q + (size_t)row * nq + head * dh + i);
+    __syncthreads();
+    const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)max_seq_len * dh;
+    const T* kc = kcache + cbase;
+    const T* vc = vcache + cbase;
+    const T* kown = k + (size_t)nd.row0 * nkv + kvh * dh;
+    const T* vown = v + (size_t)nd.row0 * nkv + kvh * dh;
+    const int n_keys = nd.S + nd.blen;
+    const float scale = 1.0f / sqrtf((float)dh);
+    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int t0 = 0; t0 < n_keys; t0 += 64) {
+        const int j = t0 + lane;
+        float s = -INFINITY;
+        if (j < n_keys) {
+            const T* kp = j < nd.S ? kc + (size_t)j * dh : kown + (size_t)(j - nd.S) * nkv;
+            float acc = 0.f;
+            for (int i = 0; i < dh; ++i) acc += qs[i] * ld_f(kp + i);
+            s = acc * scale;
+        }
+        const float m_new = fmaxf(m, wave_max(s));
+        const float p = j < n_keys ? expf(s - m_new) : 0.f;
+        const float corr = expf(m - m_new);
+        l = l * corr + wave_sum(p);
+        o0 *= corr;
+        o1 *= corr;
+        const int cnt = min(64, n_keys - t0);
+        for (int jj = 0; jj < cnt; ++jj) {
+            const float pj = __shfl(p, jj, 64);
+            const int jk = t0 + jj;
+            const T* vp = jk < nd.S ? vc + (size_t)jk * dh : vown + (size_t)(jk - nd.S) * nkv;
+            o0 += pj * ld_f(vp + lane);
+            if (dh > 64) o1 += pj * ld_f(vp + lane + 64);
+        }
+        m = m_new;
+    }
+    T* op = out + (size_t)row * nq + head * dh;
+    st_f(op + lane, o0 / l);
+    if (dh > 64) st_f(op + lane + 64, o1 / l);
+}
+
+// ------------------------------------------------------------------------
+// Plain tiled GEMM  out[M,N] = X[M,K] * W[N,K]^T, fp32 accumulation in
+// ascending k.  64x64 tile per work-group, 4x4 outputs per thread.
+// ------------------------------------------------------------------------
+#define PBM 64
+#define PBN 64
+#define PBK 16
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_plain(const T* __restrict__ X, const T* __restrict__ W,
+                                                    void* __restrict__ outv, int M, int N, int K, int up_off,
+                                                    int mask_id, int n_tiles) {
+    __shared__ float Xs[PBK][PBM + 4];
+    __shared__ float Ws[PBK][PBN + 4];
+    __shared__ float Us[EPI == EPI_SWIGLU ? PBK : 1][PBN + 4];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * PBM, n0 = blockIdx.x * PBN;
+    const int lr = tid >> 2, lk = (tid & 3) * 4;
+    float acc[4][4] = {}, accu[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += PBK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kk = k0 + lk + i;
+            const bool kin = kk < K;
+            Xs[lk + i][lr] = (kin && m0 + lr < M) ? ld_f(X + (size_t)(m0 + lr) * K + kk) : 0.f;
+            Ws[lk + i][lr] = (kin && n0 + lr < N) ? ld_f(W + (size_t)(n0 + lr) * K + kk) : 0.f;
+            if (EPI == EPI_SWIGLU)
+                Us[lk + i][lr] = (kin && n0 + lr < N) ? ld_f(W + (size_t)(up_off + n0 + lr) * K + kk) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < PBK; ++kk) {
+            float a[4], b[4], u[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = Xs[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx * 4 + j];
+            if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) u[j] = Us[kk][tx * 4 + j];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] += a[i] * b[j];
+                    if (EPI == EPI_SWIGLU) accu[i][j] += a[i] * u[j];
+                }
+        }
+        __syncthreads();
+    }
+    if (EPI == EPI_F32) {
+        float* out = (float*)outv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+                if (m < M && n < N) out[(size_t)m * N + n] = acc[i][j];
+            }
+    } else if (EPI == EPI_SWIGLU) {
+        T* out = (T*)outv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+                if (m < M && n < N) {
+                    const float g = acc[i][j];
+                    st_f(out + (size_t)m * N + n, g / (1.0f + expf(-g)) * accu[i][j]);
+                }
+            }
+    } else {
+        // fused LM-head reduction: per row, over this tile's 64 vocabulary
+        // columns: max logit, its lowest index, sum of exp(logit - max).  The
+        // mask token takes no part.  The 16 threads of a row are 16 adjacent lanes.
+        float* out = (float*)outv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float bm = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = n0 + tx * 4 + j;
+                if (n < N && n != mask_id && acc[i][j] > bm) { bm = acc[i][j]; bi = n; }
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) {
+                const float om = __shfl_xor(bm, off, 64);
+                const int oi = __shfl_xor(bi, off, 64);
+                if (om > bm || (om == bm && oi < bi)) { bm = om; bi = oi; }
+            }
+            float se = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = n0 + tx * 4 + j;
+                if (n < N && n != mask_id) se += expf(acc[i][j] - bm);
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) se += __shfl_xor(se, off, 64);
+            const int m = m0 + ty * 4 + i;
+            if (tx == 0 && m < M) {
+                float* o = out + ((size_t)m * n_tiles + blockIdx.x) * 3;
+                o[0] = bm;
+                o[1] = __int_as_float(bi);
+                o[2] = se;
+            }
+        }
+    }
+}
+
+// Merge the per-tile (max, arg, sumexp) triples of a row in a fixed order:
+// each lane folds tiles lane, lane+64, ... in ascending order, then the 64
+// lanes are folded by a butterfly.  Ties keep the lowest token id.
+__device__ __forceinline__ void lm_fold(float& m, int& a, float& s, float om, int oa, float os) {
+    if (os == 0.f) return;                 // empty partner
+    if (s == 0.f) { m = om; a = oa; s = os; return; }
+    const float nm = fmaxf(m, om);
+    s = s * expf(m - nm) + os * expf(om - nm);
+    if (om > m || (om == m && oa < a)) a = oa;
+    m = nm;
+}
+
+__global__ __launch_bounds__(64) void k_lm_merge(const float* __restrict__ part, int n_tiles,
+                                                 float* __restrict__ row_max, int* __restrict__ row_arg,
+                                                 float* __restrict__ row_conf) {
+    const int row = blockIdx.x, lane = threadIdx.x;
+    float m = -INFINITY, s = 0.f;
+    int a = 0x7fffffff;
+    for (int t = lane; t < n_tiles; t += 64) {
+        const float* p = part + ((size_t)row * n_tiles + t) * 3;
+        lm_fold(m, a, s, p[0], __float_as_int(p[1]), p[2]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float om = __shfl_xor(m, off, 64), os = __shfl_xor(s, off, 64);
+        const int oa = __shfl_xor(a, off, 64);
+        // fold (lower lane, higher lane) in the same order on both sides
+        if (lane & off) {
+            float tm = om, ts = os;
+            int ta = oa;
+            lm_fold(tm, ta, ts, m, a, s);
+            m = tm; a = ta; s = ts;
+        } else {
+            lm_fold(m, a, s, om, oa, os);
+        }
+    }
+    if (lane == 0) {
+        row_max[row] = m;
+        row_arg[row] = a;
+        row_conf[row] = 1.0f / s;          // softmax probability of the arg-max (Section 3.2.2)
+    }
+}
+
+// ------------------------------------------------------------------------
+// a11: acceptance (Section 3.2.4).  One wave per decode group, one lane per
+// block position.  Walks the chain: node m's stepwise choice (most confident
+// masked position, ties to the lowest position) must equal draft m+1 in
+// position and token; stops at the first mismatch; accepts the matched drafts
+// plus the choice of the node it stopped at; ranks that node's remaining
+// masked positions by confidence for the next drafts; commits to the state.
+// ------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
+                                               const float* __restrict__ row_conf, const int* __restrict__ row_arg,
+                                               const float* __restrict__ row_max, StepResult* __restrict__ result,
+                                               ssd_step_out out, int blockB, int maxDraft) {
+    const int gi = blockIdx.x, lane = threadIdx.x;
+    const GroupDesc g = fw->groups[gi];
+    if (g.mode != GM_DECODE) return;
+    SeqState* s = &state[g.seq];
+    const int nd = g.n_nodes - 1;
+    const int blen = g.blen;
+    const int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
+    const int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
+    unsigned long long cur = s->masked;
+    __syncthreads();
+
+    if (lane < blen) {
+        for (int j = 0; j <= nd; ++j) {
+            const int row = g.row0 + j * blen + lane;
+            const size_t o = ((size_t)gi * (maxDraft + 1) + j) * blockB + lane;
+            if (out.row_maxlogit) out.row_maxlogit[o] = row_max[row];
+            if (out.row_argmax) out.row_argmax[o] = row_arg[row];
+            if (out.row_conf) out.row_conf[o] = row_conf[row];
+        }
+    }
+
+    int m = 0, pstar = 0, tstar = 0;
+    float c = -1.f;
+    while (true) {
+        const int row = g.row0 + m * blen + lane;
+        const bool valid = lane < blen && ((cur >> lane) & 1ull);
+        c = valid ? row_conf[row] : -1.f;
+        float bc = c;
+        int bp = lane;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float oc = __shfl_xor(bc, off, 64);
+            const int op = __shfl_xor(bp, off, 64);
+            if (oc > bc || (oc == bc && op < bp)) { bc = oc; bp = op; }
+        }
+        pstar = bp;
+        tstar = row_arg[g.row0 + m * blen + pstar];
+        const int dp = __shfl(my_dpos, m, 64), dt = __shfl(my_dtok, m, 64);
+        if (m < nd && pstar == dp && tstar == dt) {
+            cur &= ~(1ull << pstar);
+            ++m;
+            continue;
+        }
+        break;
+    }
+    const unsigned long long rem = cur & ~(1ull << pstar);
+    const int n_rem = __popcll(rem);
+    const int n_next = min(g.n_draft_next, max(n_rem - 1, 0));
+    const bool mine = (rem >> lane) & 1ull;
+    int rank = 0;
+    for (int qd = 0; qd < 64; ++qd) {
+        const float cq = __shfl(c, qd, 64);
+        if (((rem >> qd) & 1ull) && (cq > c || (cq == c && qd < lane))) ++rank;
+    }
+    const int my_tok = row_arg[g.row0 + m * blen + (lane < blen ? lane : 0)];
+    StepResult* r = &result[g.seq];
+    if (mine && rank < n_next) {
+        r->next_pos[rank] = lane;
+        r->next_tok[rank] = my_tok;
+        s->draft_pos[rank] = lane;
+        s->draft_tok[rank] = my_tok;
+        if (out.next_pos) out.next_pos[(size_t)gi * maxDraft + rank] = lane;
+        if (out.next_tok) out.next_tok[(size_t)gi * maxDraft + rank] = my_tok;
+    }
+    if (lane <= m) {
+        const int ap = lane < m ? my_dpos : pstar;
+        const int at = lane < m ? my_dtok : tstar;
+        r->acc_pos[lane] = ap;
+        r->acc_tok[lane] = at;
+        s->tok[ap] = at;
+        if (out.acc_pos) out.acc_pos[(size_t)gi * (maxDraft + 1) + lane] = ap;
+        if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + lane] = at;
+    }
+    if (lane == 0) {
+        r->n_accept = m + 1;
+        r->n_next = n_next;
+        s->masked = rem;
+        s->n_draft = n_next;
+        if (out.n_accept) out.n_accept[gi] = m + 1;
+        if (out.n_next) out.n_next[gi] = n_next;
+    }
+}
+
+// ------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------
+void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes) {
+    k_build_rows<<<n_nodes, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.raw_tok, c->b.row_tok, c->b.row_pos,
+                                         c->b.row_node, c->b.out_tok, c->dm.mask_id, c->dm.max_seq_len);
+}
+
+void launch_embed(const ssd_ctx* c, int M, hipStream_t st) {
+    if (c->dm.dtype == SSD_F32)
+        k_embed<float><<<M, 256, 0, st>>>((const float*)c->embed, c->b.row_tok, c->b.h, c->dm.d);
+    else
+        k_embed<bf16_t><<<M, 256, 0, st>>>((const bf16_t*)c->embed, c->b.row_tok, c->b.h, c->dm.d);
+}
+
+void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st) {
+    const size_t stride = (size_t)c->dm.max_rows * c->dm.d;
+    if (c->dm.dtype == SSD_F32)
+        k_norm<float><<<M, 256, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (float*)c->b.xn, c->dm.d, c->dm.eps);
+    else
+        k_norm<bf16_t><<<M, 256, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (bf16_t*)c->b.xn, c->dm.d,
+                                          c->dm.eps);
+}
+
+void launch_rope(const ssd_ctx* c, int M, int layer, hipStream_t st) {
+    const Dims& d = c->dm;
+    if (d.dtype == SSD_F32)
+        k_rope<float><<<M, 256, 0, st>>>(c->b.fwd, c->b.qkv, c->b.row_pos, c->b.row_node, c->b.rope_cos,
+                                         c->b.rope_sin, (float*)c->b.q, (float*)c->b.k, (float*)c->b.v,
+                                         (float*)c->b.kcache, (float*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
+                                         d.max_seqs, d.max_seq_len);
+    else
+        k_rope<bf16_t><<<M, 256, 0, st>>>(c->b.fwd, c->b.qkv, c->b.row_pos, c->b.row_node, c->b.rope_cos,
+                                          c->b.rope_sin, (bf16_t*)c->b.q, (bf16_t*)c->b.k, (bf16_t*)c->b.v,
+                                          (bf16_t*)c->b.kcache, (bf16_t*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
+                                          d.max_seqs, d.max_seq_len);
+}
+
+void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st) {
+    const Dims& d = c->dm;
+    dim3 grid(M, d.Hq);
+    if (d.dtype == SSD_F32)
+        k_attn_plain<float><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const float*)c->b.q, (const float*)c->b.k,
+                                                 (const float*)c->b.v, (const float*)c->b.kcache,
+                                                 (const float*)c->b.vcache, (float*)c->b.attn, d.Hq, d.Hkv, d.dh,
+                                                 layer, d.max_seqs, d.max_seq_len);
+    else
+        k_attn_plain<bf16_t><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const bf16_t*)c->b.q,
+                                                  (const bf16_t*)c->b.k, (const bf16_t*)c->b.v,
+                                                  (const bf16_t*)c->b.kcache, (const bf16_t*)c->b.vcache,
+                                                  (bf16_t*)c->b.attn, d.Hq, d.Hkv, d.dh, layer, d.max_seqs,
+                                                  d.max_seq_len);
+}
+
+template <typename T>
+static void gemm_plain_t(const ssd_ctx* c, int epi, const T* X, const T* W, void* out, int M, int N, int K,
+                         hipStream_t st) {
+    dim3 grid((N + PBN - 1) / PBN, (M + PBM - 1) / PBM);
+    if (epi == EPI_F32)
+        k_gemm_plain<T, EPI_F32><<<grid, 256, 0, st>>>(X, W, out, M, N, K, 0, -1, 0);
+    else if (epi == EPI_SWIGLU)
+        k_gemm_plain<T, EPI_SWIGLU><<<grid, 256, 0, st>>>(X, W, out, M, N, K, N, -1, 0);
+    else
+        k_gemm_plain<T, EPI_LMHEAD><<<grid, 256, 0, st>>>(X, W, out, M, N, K, 0, c->dm.mask_id, (int)grid.x);
+}
+
+void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, void* out, int M, int N, int K,
+                       hipStream_t st) {
+    if (c->dm.dtype == SSD_F32)
+        gemm_plain_t<float>(c, epi, (const float*)X, (const float*)W, out, M, N, K, st);
+    else
+        gemm_plain_t<bf16_t>(c, epi, (const bf16_t*)X, (const bf16_t*)W, out, M, N, K, st);
+}
+
+int lm_tiles_plain(int V) { return (V + PBN - 1) / PBN; }
+
+void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
+    k_lm_merge<<<M, 64, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf);
+}
+
+void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st) {
+    ssd_step_out o = {};
+    if (out) o = *out;
+    k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result, o,
+                                      c->dm.block, c->dm.max_draft);
+}

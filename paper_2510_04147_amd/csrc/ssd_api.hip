@@ -1,0 +1,589 @@
+// Host side of the C ABI: validation, workspace carve-up, the forward driver
+// (one pass of the transformer over a list of node groups) and the decoding
+// loop of Algorithm 1.  All arithmetic of the method runs in the kernels; the
+// host only decides which forward to launch next.
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ssd_internal.h"
+
+#define HIPCHK(ctx, call)                                                                   \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            set_err(ctx, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return SSD_EHIP;                                                                \
+        }                                                                                   \
+    } while (0)
+
+static void set_err(ssd_ctx* c, const char* fmt, ...) {
+    if (!c) return;
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    c->err = buf;
+}
+
+static thread_local std::string g_create_err;
+
+extern "C" __attribute__((visibility("default"))) const char* ssd_strerror(int code) {
+    switch (code) {
+        case SSD_OK: return "ok";
+        case SSD_EINVAL: return "invalid argument";
+        case SSD_ERANGE: return "size or index out of range for this context";
+        case SSD_ENOMEM: return "workspace too small";
+        case SSD_EHIP: return "HIP runtime error";
+        case SSD_ESTATE: return "call does not fit the cached prefix";
+        default: return "unknown error";
+    }
+}
+
+extern "C" __attribute__((visibility("default"))) const char* ssd_last_error(const ssd_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+
+// ------------------------------------------------------------------ config
+static int check_config(const ssd_config* cfg, std::string* why) {
+    auto bad = [&](int code, const char* m) { *why = m; return code; };
+    if (!cfg) return bad(SSD_EINVAL, "null config");
+    if (cfg->n_layers < 1 || cfg->d_model < 8 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1 || cfg->d_ffn < 8 ||
+        cfg->vocab < 2 || cfg->max_seqs < 1 || cfg->max_seq_len < 1 || cfg->block < 1 || cfg->max_draft < 0 ||
+        cfg->max_rows < 1)
+        return bad(SSD_EINVAL, "non-positive dimension");
+    if (cfg->dtype != SSD_F32 && cfg->dtype != SSD_BF16) return bad(SSD_EINVAL, "dtype must be SSD_F32 or SSD_BF16");
+    if (cfg->n_q_heads % cfg->n_kv_heads) return bad(SSD_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    if (cfg->head_dim != 64 && cfg->head_dim != 128) return bad(SSD_ERANGE, "head_dim must be 64 or 128");
+    if (cfg->d_model % 8 || cfg->d_ffn % 8) return bad(SSD_EINVAL, "d_model and d_ffn must be multiples of 8");
+    if (cfg->mask_id < 0 || cfg->mask_id >= cfg->vocab) return bad(SSD_EINVAL, "mask_id outside the vocabulary");
+    if (cfg->block > SSD_MAX_BLOCK) return bad(SSD_ERANGE, "block exceeds SSD_MAX_BLOCK");
+    if (cfg->max_draft > SSD_MAX_DRAFT) return bad(SSD_ERANGE, "max_draft exceeds SSD_MAX_DRAFT");
+    if (cfg->max_seqs > SSD_MAX_SEQS) return bad(SSD_ERANGE, "max_seqs exceeds 16");
+    if ((long long)cfg->max_seqs * (cfg->max_draft + 1) * cfg->block > cfg->max_rows)
+        return bad(SSD_EINVAL, "max_rows smaller than max_seqs*(max_draft+1)*block");
+    if (!(cfg->rope_theta > 0.f) || !(cfg->rms_eps >= 0.f)) return bad(SSD_EINVAL, "bad rope_theta / rms_eps");
+    return SSD_OK;
+}
+
+static Dims dims_of(const ssd_config* c) {
+    Dims d;
+    d.L = c->n_layers; d.d = c->d_model; d.Hq = c->n_q_heads; d.Hkv = c->n_kv_heads; d.dh = c->head_dim;
+    d.F = c->d_ffn; d.V = c->vocab; d.mask_id = c->mask_id; d.dtype = c->dtype; d.eps = c->rms_eps;
+    d.max_seqs = c->max_seqs; d.max_seq_len = c->max_seq_len; d.block = c->block; d.max_draft = c->max_draft;
+    d.max_rows = c->max_rows;
+    return d;
+}
+
+// the plain kernel has the finest vocabulary tiling, so its tile count bounds every path's
+static int lm_tiles_for(const Dims& d) { return lm_tiles_plain(d.V); }
+
+// Walks the workspace layout; with base == nullptr it only measures.
+static size_t carve(const Dims& d, char* base, Buffers* b) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> void* {
+        off = (off + 255) & ~(size_t)255;
+        void* p = base ? base + off : nullptr;
+        off += bytes;
+        return p;
+    };
+    const size_t R = d.max_rows, e = d.esz();
+    const int tiles = lm_tiles_for(d);
+    Buffers t;
+    t.h = (float*)take(R * d.d * 4);
+    t.xn = take(R * d.d * e);
+    t.qkv = (float*)take(R * d.nqkv() * 4);
+    t.q = take(R * d.nq() * e);
+    t.k = take(R * d.nkv() * e);
+    t.v = take(R * d.nkv() * e);
+    t.attn = take(R * d.nq() * e);
+    t.act = take(R * d.F * e);
+    t.part = (float*)take((size_t)SSD_MAX_SPLIT * R * d.d * 4);
+    t.lm_part = (float*)take(R * (size_t)tiles * 3 * 4);
+    t.row_max = (float*)take(R * 4);
+    t.row_arg = (int*)take(R * 4);
+    t.row_conf = (float*)take(R * 4);
+    t.row_tok = (int*)take(R * 4);
+    t.row_pos = (int*)take(R * 4);
+    t.row_node = (int*)take(R * 4);
+    t.raw_tok = (int*)take(R * 4);
+    const size_t cache = (size_t)d.L * d.max_seqs * d.Hkv * d.max_seq_len * d.dh * e;
+    t.kcache = take(cache);
+    t.vcache = take(cache);
+    t.rope_cos = (float*)take((size_t)d.max_seq_len * (d.dh / 2) * 4);
+    t.rope_sin = (float*)take((size_t)d.max_seq_len * (d.dh / 2) * 4);
+    t.fwd = (FwdHeader*)take(sizeof(FwdHeader));
+    t.state = (SeqState*)take(sizeof(SeqState) * SSD_MAX_SEQS);
+    t.result = (StepResult*)take(sizeof(StepResult) * SSD_MAX_SEQS);
+    t.out_tok = (int*)take((size_t)d.max_seqs * d.max_seq_len * 4);
+    t.lm_tiles = tiles;
+    if (b) *b = t;
+    return (off + 255) & ~(size_t)255;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t ssd_workspace_bytes(const ssd_config* cfg) {
+    std::string why;
+    if (check_config(cfg, &why) != SSD_OK) return 0;
+    return carve(dims_of(cfg), nullptr, nullptr);
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_config* cfg, const ssd_weights* w, void* workspace, size_t ws_bytes,
+                          void* hip_stream, ssd_ctx** out) {
+    std::string why;
+    int rc = check_config(cfg, &why);
+    if (rc != SSD_OK) { g_create_err = why; return rc; }
+    if (!w || !out || !workspace) { g_create_err = "null weights / workspace / out"; return SSD_EINVAL; }
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->wqkv || !w->wo || !w->wgu || !w->wdown || !w->norm1 ||
+        !w->norm2) { g_create_err = "null weight pointer"; return SSD_EINVAL; }
+    if (((uintptr_t)workspace) & 255) { g_create_err = "workspace must be 256-byte aligned"; return SSD_EINVAL; }
+    const Dims d = dims_of(cfg);
+    const size_t need = carve(d, nullptr, nullptr);
+    if (ws_bytes < need) { g_create_err = "workspace smaller than ssd_workspace_bytes()"; return SSD_ENOMEM; }
+    for (int l = 0; l < d.L; ++l)
+        if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wdown[l] || !w->norm1[l] || !w->norm2[l]) {
+            g_create_err = "null per-layer weight pointer";
+            return SSD_EINVAL;
+        }
+    ssd_ctx* c = new (std::nothrow) ssd_ctx();
+    if (!c) { g_create_err = "host allocation failed"; return SSD_ENOMEM; }
+    c->dm = d;
+    carve(d, (char*)workspace, &c->b);
+    c->lw.resize(d.L);
+    for (int l = 0; l < d.L; ++l)
+        c->lw[l] = LayerW{w->wqkv[l], w->wo[l], w->wgu[l], w->wdown[l], w->norm1[l], w->norm2[l]};
+    c->embed = w->embed; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
+    c->stream = (hipStream_t)hip_stream;
+    c->kernel_path = 1;
+    memset(c->cached_len, 0, sizeof c->cached_len);
+    c->profiling = false; c->ev_used = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms); memset(c->prof_n, 0, sizeof c->prof_n);
+    c->stage_next = 0;
+    c->stage_bytes = sizeof(FwdHeader) + (size_t)d.max_rows * 4 + sizeof(SeqState) * SSD_MAX_SEQS;
+    for (int i = 0; i < ssd_ctx::kSlots; ++i) { c->stage[i] = nullptr; c->stage_ev[i] = nullptr; c->stage_used[i] = false; }
+    c->host_result = nullptr;
+    auto fail = [&](hipError_t e, const char* what) {
+        g_create_err = std::string(what) + ": " + hipGetErrorString(e);
+        ssd_destroy(c);
+        return SSD_EHIP;
+    };
+    hipError_t e;
+    for (int i = 0; i < ssd_ctx::kSlots; ++i) {
+        if ((e = hipHostMalloc((void**)&c->stage[i], c->stage_bytes, hipHostMallocDefault)) != hipSuccess)
+            return fail(e, "hipHostMalloc(staging)");
+        if ((e = hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming)) != hipSuccess)
+            return fail(e, "hipEventCreate");
+    }
+    if ((e = hipHostMalloc((void**)&c->host_result, sizeof(StepResult) * SSD_MAX_SEQS, hipHostMallocDefault)) != hipSuccess)
+        return fail(e, "hipHostMalloc(result)");
+    // rotary table in double precision: angle(pos, i) = pos * theta^(-2i/dh)
+    {
+        const int half = d.dh / 2;
+        std::vector<float> cs((size_t)d.max_seq_len * half), sn((size_t)d.max_seq_len * half);
+        for (int i = 0; i < half; ++i) {
+            const double inv = std::pow((double)cfg->rope_theta, -2.0 * i / d.dh);
+            for (int p = 0; p < d.max_seq_len; ++p) {
+                const double a = (double)p * inv;
+                cs[(size_t)p * half + i] = (float)std::cos(a);
+                sn[(size_t)p * half + i] = (float)std::sin(a);
+            }
+        }
+        if ((e = hipMemcpy(c->b.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice)) != hipSuccess)
+            return fail(e, "hipMemcpy(rope)");
+        if ((e = hipMemcpy(c->b.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice)) != hipSuccess)
+            return fail(e, "hipMemcpy(rope)");
+        if ((e = hipMemset(c->b.state, 0, sizeof(SeqState) * SSD_MAX_SEQS)) != hipSuccess) return fail(e, "hipMemset");
+        if ((e = hipMemset(c->b.result, 0, sizeof(StepResult) * SSD_MAX_SEQS)) != hipSuccess) return fail(e, "hipMemset");
+    }
+    *out = c;
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_destroy(ssd_ctx* c) {
+    if (!c) return SSD_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    for (int i = 0; i < ssd_ctx::kSlots; ++i) {
+        if (c->stage[i]) (void)hipHostFree(c->stage[i]);
+        if (c->stage_ev[i]) (void)hipEventDestroy(c->stage_ev[i]);
+    }
+    if (c->host_result) (void)hipHostFree(c->host_result);
+    for (auto ev : c->ev_pool) (void)hipEventDestroy(ev);
+    delete c;
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_reset(ssd_ctx* c, int seq) {
+    if (!c) return SSD_EINVAL;
+    if (seq < 0 || seq >= c->dm.max_seqs) { set_err(c, "seq %d out of range", seq); return SSD_ERANGE; }
+    c->cached_len[seq] = 0;
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_cached_len(ssd_ctx* c, int seq) {
+    if (!c) return SSD_EINVAL;
+    if (seq < 0 || seq >= c->dm.max_seqs) { set_err(c, "seq %d out of range", seq); return SSD_ERANGE; }
+    return c->cached_len[seq];
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_kernel_path(ssd_ctx* c, int path) {
+    if (!c || (path != 0 && path != 1)) return SSD_EINVAL;
+    const int old = c->kernel_path;
+    c->kernel_path = path;
+    return old;
+}
+
+// --------------------------------------------------------------- profiling
+static const char* kClassNames[KC_COUNT] = {"build_rows+embed", "rmsnorm", "gemm_qkv", "rope", "attention", "gemm_o",
+                                            "gemm_gate_up_swiglu", "gemm_down", "lm_head_reduce", "lm_merge",
+                                            "accept"};
+
+struct ProfScope {
+    ssd_ctx* c;
+    bool on;
+    size_t idx;
+    ProfScope(ssd_ctx* c_, int cls) : c(c_), on(c_->profiling), idx(0) {
+        if (!on) return;
+        while (c->ev_pool.size() < c->ev_used + 2) {
+            hipEvent_t ev;
+            if (hipEventCreate(&ev) != hipSuccess) { on = false; return; }
+            c->ev_pool.push_back(ev);
+            c->ev_class.push_back(0);
+        }
+        idx = c->ev_used;
+        c->ev_used += 2;
+        c->ev_class[idx] = cls;
+        (void)hipEventRecord(c->ev_pool[idx], c->stream);
+    }
+    ~ProfScope() {
+        if (on) (void)hipEventRecord(c->ev_pool[idx + 1], c->stream);
+    }
+};
+
+static void prof_collect(ssd_ctx* c) {
+    (void)hipStreamSynchronize(c->stream);
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->ev_pool[i], c->ev_pool[i + 1]) == hipSuccess) {
+            c->prof_ms[c->ev_class[i]] += ms;
+            c->prof_n[c->ev_class[i]] += 1;
+        }
+    }
+    c->ev_used = 0;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_profile_begin(ssd_ctx* c) {
+    if (!c) return SSD_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    c->profiling = true;
+    c->ev_used = 0;
+    memset(c->prof_ms, 0, sizeof c->prof_ms);
+    memset(c->prof_n, 0, sizeof c->prof_n);
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_profile_read(ssd_ctx* c, int* n_classes, const char** names, int64_t* launches, double* ms) {
+    if (!c || !n_classes) return SSD_EINVAL;
+    prof_collect(c);
+    const int cap = *n_classes;
+    for (int i = 0; i < KC_COUNT && i < cap; ++i) {
+        if (names) names[i] = kClassNames[i];
+        if (launches) launches[i] = c->prof_n[i];
+        if (ms) ms[i] = c->prof_ms[i];
+    }
+    *n_classes = KC_COUNT;
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_profile_end(ssd_ctx* c) {
+    if (!c) return SSD_EINVAL;
+    prof_collect(c);
+    c->profiling = false;
+    return SSD_OK;
+}
+
+// ---------------------------------------------------------- forward driver
+struct Upload {           // block state to push before the forward (stateless API)
+    int seq;
+    SeqState st;
+};
+
+static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const void* W, void* out, int M, int N, int K,
+                 int* n_split) {
+    ProfScope ps(c, cls);
+    *n_split = 1;
+    if (c->kernel_path == 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, N, K, n_split, c->stream))
+        return;
+    *n_split = epi == EPI_LMHEAD ? lm_tiles_plain(N) : 1;
+    launch_gemm_plain(c, epi, X, W, out, M, N, K, c->stream);
+}
+
+// Runs one forward over the groups in `hd` (decode groups first).  raw / n_raw:
+// tokens of GM_RAW groups; ups: block states to upload first.
+static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int n_raw, const Upload* ups, int n_ups,
+                       const ssd_step_out* out) {
+    const Dims& d = c->dm;
+    hipStream_t st = c->stream;
+    // ---- stage and upload the descriptor
+    const int slot = c->stage_next;
+    c->stage_next = (slot + 1) % ssd_ctx::kSlots;
+    if (c->stage_used[slot]) HIPCHK(c, hipEventSynchronize(c->stage_ev[slot]));
+    char* sp = c->stage[slot];
+    memcpy(sp, &hd, sizeof hd);
+    HIPCHK(c, hipMemcpyAsync(c->b.fwd, sp, sizeof hd, hipMemcpyHostToDevice, st));
+    if (n_raw > 0) {
+        int* sr = (int*)(sp + sizeof(FwdHeader));
+        memcpy(sr, raw, (size_t)n_raw * 4);
+        HIPCHK(c, hipMemcpyAsync(c->b.raw_tok, sr, (size_t)n_raw * 4, hipMemcpyHostToDevice, st));
+    }
+    if (n_ups > 0) {
+        SeqState* ss = (SeqState*)(sp + sizeof(FwdHeader) + (size_t)d.max_rows * 4);
+        for (int i = 0; i < n_ups; ++i) {
+            ss[i] = ups[i].st;
+            HIPCHK(c, hipMemcpyAsync(&c->b.state[ups[i].seq], &ss[i], sizeof(SeqState), hipMemcpyHostToDevice, st));
+        }
+    }
+    HIPCHK(c, hipEventRecord(c->stage_ev[slot], st));
+    c->stage_used[slot] = true;
+
+    const int M = hd.M, ML = hd.M_logits;
+    {
+        ProfScope ps(c, KC_ROWS);
+        launch_build_rows(c, st, hd.n_nodes);
+        launch_embed(c, M, st);
+    }
+    int n_part = 0, ns = 1;
+    for (int l = 0; l < d.L; ++l) {
+        const LayerW& w = c->lw[l];
+        { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
+        n_part = 0;
+        gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.qkv, M, d.nqkv(), d.d, &ns);
+        { ProfScope ps(c, KC_ROPE); launch_rope(c, M, l, st); }
+        if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
+        {
+            ProfScope ps(c, KC_ATTN);
+            if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, M, l, st)))
+                launch_attn_plain(c, M, l, st);
+        }
+        gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, d.d, d.nq(), &ns);
+        { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm2, ns, st); }
+        gemm(c, KC_GEMM_GU, EPI_SWIGLU, c->b.xn, w.wgu, c->b.act, M, d.F, d.d, &ns);
+        gemm(c, KC_GEMM_DOWN, EPI_F32, c->b.act, w.wdown, c->b.part, M, d.d, d.F, &ns);
+        n_part = ns;
+    }
+    if (ML > 0) {
+        { ProfScope ps(c, KC_NORM); launch_norm(c, ML, c->final_norm, n_part, st); }
+        int tiles = 0;
+        gemm(c, KC_LMHEAD, EPI_LMHEAD, c->b.xn, c->lm_head, c->b.lm_part, ML, d.V, d.d, &tiles);
+        { ProfScope ps(c, KC_LMMERGE); launch_lm_merge(c, ML, tiles, st); }
+        { ProfScope ps(c, KC_ACCEPT); launch_accept(c, hd.n_groups, out, st); }
+    }
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
+}
+
+// Appends a group (and its nodes) to a header; returns the rows it takes.
+static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_nodes, int n_draft_next, int fresh,
+                     int raw_off, int out_off) {
+    GroupDesc& g = hd.groups[hd.n_groups];
+    g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
+    g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.pad = 0;
+    for (int j = 0; j < n_nodes; ++j) {
+        NodeDesc& nd = hd.nodes[hd.n_nodes++];
+        nd.seq = seq; nd.row0 = hd.M + j * blen; nd.blen = blen; nd.S = S; nd.group = hd.n_groups; nd.j = j;
+        nd.write_kv = mode != GM_DECODE; nd.pad = 0;
+    }
+    hd.n_groups++;
+    hd.M += n_nodes * blen;
+    if (mode == GM_DECODE) hd.M_logits = hd.M;
+    return n_nodes * blen;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_prefill_kv(ssd_ctx* c, int seq, const int32_t* tokens, int n, int pos0) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!tokens || n < 1 || pos0 < 0) { set_err(c, "prefill: null tokens, n < 1 or pos0 < 0"); return SSD_EINVAL; }
+    if (seq < 0 || seq >= d.max_seqs) { set_err(c, "prefill: seq %d out of range", seq); return SSD_ERANGE; }
+    if (n > d.max_rows) { set_err(c, "prefill: %d rows exceed max_rows %d", n, d.max_rows); return SSD_ERANGE; }
+    if ((long long)pos0 + n > d.max_seq_len) { set_err(c, "prefill: pos0+n exceeds max_seq_len"); return SSD_ERANGE; }
+    if (pos0 > c->cached_len[seq]) {
+        set_err(c, "prefill: pos0 %d beyond the cached prefix %d", pos0, c->cached_len[seq]);
+        return SSD_ESTATE;
+    }
+    for (int i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= d.V) { set_err(c, "prefill: token id %d out of range", tokens[i]); return SSD_ERANGE; }
+    FwdHeader hd;
+    memset(&hd, 0, sizeof hd);
+    add_group(hd, seq, GM_RAW, n, pos0, 1, 0, 0, 0, -1);
+    int rc = run_forward(c, hd, tokens, n, nullptr, 0, nullptr);
+    if (rc == SSD_OK) c->cached_len[seq] = pos0 + n;
+    return rc;
+}
+
+static int popcount64(uint64_t x) { return __builtin_popcountll(x); }
+
+static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, const int32_t* block_tok,
+                       const uint64_t* masked, const int* pos0, const int* block_len, const int32_t* draft_pos,
+                       const int32_t* draft_tok, const int* n_draft, int n_draft_next, const ssd_step_out* out) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (n < 1 || !seqs || !block_tok || !masked || !pos0) { set_err(c, "%s: null argument or n < 1", who); return SSD_EINVAL; }
+    if (n > d.max_seqs) { set_err(c, "%s: n %d exceeds max_seqs", who, n); return SSD_ERANGE; }
+    if (n_draft_next < 0 || n_draft_next > d.max_draft) { set_err(c, "%s: n_draft_next out of range", who); return SSD_ERANGE; }
+    FwdHeader hd;
+    memset(&hd, 0, sizeof hd);
+    Upload ups[SSD_MAX_SEQS];
+    bool seen[SSD_MAX_SEQS] = {};
+    for (int i = 0; i < n; ++i) {
+        const int seq = seqs[i];
+        if (seq < 0 || seq >= d.max_seqs) { set_err(c, "%s: seq %d out of range", who, seq); return SSD_ERANGE; }
+        if (seen[seq]) { set_err(c, "%s: seq %d listed twice", who, seq); return SSD_EINVAL; }
+        seen[seq] = true;
+        const int bl = block_len ? block_len[i] : d.block;
+        if (bl < 1 || bl > d.block) { set_err(c, "%s: block_len %d out of range", who, bl); return SSD_ERANGE; }
+        if (pos0[i] != c->cached_len[seq]) {
+            set_err(c, "%s: pos0 %d is not the cached prefix length %d of seq %d", who, pos0[i], c->cached_len[seq], seq);
+            return SSD_ESTATE;
+        }
+        if ((long long)pos0[i] + bl > d.max_seq_len) { set_err(c, "%s: block exceeds max_seq_len", who); return SSD_ERANGE; }
+        const uint64_t mk = masked[i];
+        if (bl < 64 && (mk >> bl)) { set_err(c, "%s: masked bits beyond block_len", who); return SSD_EINVAL; }
+        const int nm = popcount64(mk);
+        if (nm < 1) { set_err(c, "%s: no masked position in the block", who); return SSD_EINVAL; }
+        const int nd = n_draft ? n_draft[i] : 0;
+        if (nd < 0 || nd > d.max_draft) { set_err(c, "%s: n_draft %d out of range", who, nd); return SSD_ERANGE; }
+        if (nd > nm - 1) { set_err(c, "%s: n_draft %d leaves the leaf no masked position (%d masked)", who, nd, nm); return SSD_EINVAL; }
+        if (nd > 0 && (!draft_pos || !draft_tok)) { set_err(c, "%s: null drafts", who); return SSD_EINVAL; }
+        SeqState& s = ups[i].st;
+        memset(&s, 0, sizeof s);
+        ups[i].seq = seq;
+        s.masked = mk;
+        s.n_draft = nd;
+        for (int p = 0; p < bl; ++p) {
+            const int t = block_tok[(size_t)i * d.block + p];
+            if (t < 0 || t >= d.V) { set_err(c, "%s: token id %d out of range", who, t); return SSD_ERANGE; }
+            s.tok[p] = ((mk >> p) & 1) ? d.mask_id : t;
+        }
+        uint64_t used = 0;
+        for (int j = 0; j < nd; ++j) {
+            const int q = draft_pos[(size_t)i * d.max_draft + j], t = draft_tok[(size_t)i * d.max_draft + j];
+            if (q < 0 || q >= bl || !((mk >> q) & 1)) { set_err(c, "%s: draft position %d is not a masked position", who, q); return SSD_EINVAL; }
+            if ((used >> q) & 1) { set_err(c, "%s: draft position %d listed twice", who, q); return SSD_EINVAL; }
+            if (t < 0 || t >= d.V || t == d.mask_id) { set_err(c, "%s: draft token %d out of range", who, t); return SSD_ERANGE; }
+            used |= 1ull << q;
+            s.draft_pos[j] = q;
+            s.draft_tok[j] = t;
+        }
+        if (hd.M + (nd + 1) * bl > d.max_rows) { set_err(c, "%s: forward exceeds max_rows", who); return SSD_ERANGE; }
+        add_group(hd, seq, GM_DECODE, bl, pos0[i], nd + 1, n_draft_next, 0, 0, -1);
+    }
+    return run_forward(c, hd, nullptr, 0, ups, n, out);
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_draft(ssd_ctx* c, int n, const int* seqs, const int32_t* block_tok, const uint64_t* masked,
+                         const int* pos0, const int* block_len, int n_draft_next, const ssd_step_out* out) {
+    return step_common(c, "ssd_draft", n, seqs, block_tok, masked, pos0, block_len, nullptr, nullptr, nullptr,
+                       n_draft_next, out);
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_verify_tree(ssd_ctx* c, int n, const int* seqs, const int32_t* block_tok, const uint64_t* masked,
+                               const int* pos0, const int* block_len, const int32_t* draft_pos,
+                               const int32_t* draft_tok, const int* n_draft, int n_draft_next,
+                               const ssd_step_out* out) {
+    if (c && !n_draft) { set_err(c, "ssd_verify_tree: null n_draft"); return SSD_EINVAL; }
+    return step_common(c, "ssd_verify_tree", n, seqs, block_tok, masked, pos0, block_len, draft_pos, draft_tok,
+                       n_draft, n_draft_next, out);
+}
+
+// ------------------------------------------------------------- Algorithm 1
+extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, int n, const int32_t* const* prompts, const int* prompt_len, int gen_len,
+                            int block, int draft_depth, int32_t* out_tokens, ssd_stats* stats) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (n < 1 || !prompts || !prompt_len || !out_tokens || gen_len < 1) { set_err(c, "generate: bad argument"); return SSD_EINVAL; }
+    if (n > d.max_seqs) { set_err(c, "generate: n exceeds max_seqs"); return SSD_ERANGE; }
+    if (block < 1 || block > d.block) { set_err(c, "generate: block %d out of range", block); return SSD_ERANGE; }
+    if (draft_depth < 0 || draft_depth > d.max_draft) { set_err(c, "generate: draft_depth out of range"); return SSD_ERANGE; }
+    for (int i = 0; i < n; ++i) {
+        if (!prompts[i] || prompt_len[i] < 1) { set_err(c, "generate: empty prompt %d", i); return SSD_EINVAL; }
+        if (prompt_len[i] > d.max_rows || (long long)prompt_len[i] + gen_len > d.max_seq_len) {
+            set_err(c, "generate: prompt %d (+gen_len) exceeds max_rows / max_seq_len", i);
+            return SSD_ERANGE;
+        }
+    }
+    const auto t_begin = std::chrono::steady_clock::now();
+    ssd_stats sta;
+    memset(&sta, 0, sizeof sta);
+    hipEvent_t ev0, ev1;
+    HIPCHK(c, hipEventCreate(&ev0));
+    HIPCHK(c, hipEventCreate(&ev1));
+    auto done = [&](int rc) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return rc; };
+    int rc;
+    // prompt prefill, one segment per forward
+    for (int i = 0; i < n; ++i) {
+        c->cached_len[i] = 0;
+        (void)hipEventRecord(ev0, c->stream);
+        if ((rc = ssd_prefill_kv(c, i, prompts[i], prompt_len[i], 0)) != SSD_OK) return done(rc);
+        (void)hipEventRecord(ev1, c->stream);
+        if (hipEventSynchronize(ev1) != hipSuccess) { set_err(c, "generate: sync failed"); return done(SSD_EHIP); }
+        float ms = 0; (void)hipEventElapsedTime(&ms, ev0, ev1);
+        sta.kv_ms += ms; sta.kv_passes++;
+    }
+    const int n_blocks = (gen_len + block - 1) / block;
+    enum { FRESH, DECODE, APPEND, DONE };
+    int phase[SSD_MAX_SEQS], blk[SSD_MAX_SEQS], n_masked[SSD_MAX_SEQS], n_dr[SSD_MAX_SEQS];
+    for (int i = 0; i < n; ++i) { phase[i] = FRESH; blk[i] = 0; n_masked[i] = 0; n_dr[i] = 0; }
+    int live = n;
+    while (live > 0) {
+        FwdHeader hd;
+        memset(&hd, 0, sizeof hd);
+        bool any_decode = false;
+        for (int pass = 0; pass < 2; ++pass)          // decode groups first, then KV appends
+            for (int i = 0; i < n; ++i) {
+                if (phase[i] == DONE) continue;
+                const int bl = std::min(block, gen_len - blk[i] * block);
+                if (pass == 0 && phase[i] != APPEND) {
+                    if (phase[i] == FRESH) { n_masked[i] = bl; n_dr[i] = 0; }
+                    add_group(hd, i, GM_DECODE, bl, c->cached_len[i], n_dr[i] + 1, draft_depth, phase[i] == FRESH, 0, -1);
+                    any_decode = true;
+                } else if (pass == 1 && phase[i] == APPEND) {
+                    add_group(hd, i, GM_APPEND, bl, c->cached_len[i], 1, 0, 0, 0, blk[i] * block);
+                }
+            }
+        if (hd.M > d.max_rows) { set_err(c, "generate: forward exceeds max_rows"); return done(SSD_ERANGE); }
+        (void)hipEventRecord(ev0, c->stream);
+        if ((rc = run_forward(c, hd, nullptr, 0, nullptr, 0, nullptr)) != SSD_OK) return done(rc);
+        if (any_decode)
+            HIPCHK(c, hipMemcpyAsync(c->host_result, c->b.result, sizeof(StepResult) * d.max_seqs, hipMemcpyDeviceToHost, c->stream));
+        (void)hipEventRecord(ev1, c->stream);
+        if (hipEventSynchronize(ev1) != hipSuccess) { set_err(c, "generate: sync failed: %s", hipGetErrorString(hipGetLastError())); return done(SSD_EHIP); }
+        float ms = 0; (void)hipEventElapsedTime(&ms, ev0, ev1);
+        if (any_decode) { sta.decode_ms += ms; sta.forwards++; } else { sta.kv_ms += ms; sta.kv_passes++; }
+        for (int gi = 0; gi < hd.n_groups; ++gi) {
+            const GroupDesc& g = hd.groups[gi];
+            const int i = g.seq;
+            if (g.mode == GM_DECODE) {
+                const StepResult& r = c->host_result[i];
+                if (r.n_accept < 1 || r.n_accept > g.n_nodes || r.n_accept > n_masked[i]) {
+                    set_err(c, "generate: acceptance kernel returned %d for %d nodes", r.n_accept, g.n_nodes);
+                    return done(SSD_EHIP);
+                }
+                sta.accept_hist[r.n_accept]++;
+                sta.tokens += r.n_accept;
+                n_masked[i] -= r.n_accept;
+                n_dr[i] = r.n_next;
+                phase[i] = n_masked[i] == 0 ? APPEND : DECODE;
+            } else {
+                c->cached_len[i] += g.blen;
+                blk[i]++;
+                if (blk[i] == n_blocks) { phase[i] = DONE; live--; } else phase[i] = FRESH;
+            }
+        }
+    }
+    for (int i = 0; i < n; ++i)
+        HIPCHK(c, hipMemcpy(out_tokens + (size_t)i * gen_len, c->b.out_tok + (size_t)i * d.max_seq_len, (size_t)gen_len * 4,
+                            hipMemcpyDeviceToHost));
+    sta.total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+    if (stats) *stats = sta;
+    return done(SSD_OK);
+}

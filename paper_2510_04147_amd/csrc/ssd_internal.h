@@ -1,0 +1,159 @@
+// Internal declarations shared by the host driver and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/ssd.h"
+
+#define SSD_MAX_SEQS 16
+#define SSD_MAX_NODES (SSD_MAX_SEQS * (SSD_MAX_DRAFT + 1))
+#define SSD_MAX_SPLIT 8
+
+// ---- forward descriptor (host-built, copied to the device before each forward)
+enum GroupMode : int {
+    GM_DECODE = 0,   // chain of nodes from the device-side block state; logits + acceptance
+    GM_APPEND = 1,   // one node = the finished block from the block state; writes KV
+    GM_RAW = 2,      // one node of raw tokens (prompt prefill); writes KV
+};
+
+struct GroupDesc {
+    int seq, row0, blen, S;
+    int n_nodes, mode, raw_off, n_draft_next;
+    int fresh;      // GM_DECODE: block starts now, state = all masked, no drafts
+    int out_off;    // GM_APPEND: offset into the device token output, or -1
+    int node0;      // index of the group's first node
+    int pad;
+};
+
+struct NodeDesc {
+    int seq, row0, blen, S;
+    int group, j;   // j = index of the node inside its group = number of drafts written in
+    int write_kv, pad;
+};
+
+struct FwdHeader {
+    int n_groups, n_nodes, M, M_logits;
+    GroupDesc groups[SSD_MAX_SEQS];
+    NodeDesc nodes[SSD_MAX_NODES];
+};
+
+// Device-side block state of one sequence slot (Algorithm 1's x restricted to
+// the current block, its masked set, and the drafts d for the next round).
+struct SeqState {
+    unsigned long long masked;
+    int n_draft;
+    int pad;
+    int tok[SSD_MAX_BLOCK];
+    int draft_pos[SSD_MAX_DRAFT + 1];
+    int draft_tok[SSD_MAX_DRAFT + 1];
+};
+
+// Per-forward results of the acceptance kernel (device), mirrored to the host
+// by ssd_generate.
+struct StepResult {
+    int n_accept, n_next;
+    int acc_pos[SSD_MAX_DRAFT + 1], acc_tok[SSD_MAX_DRAFT + 1];
+    int next_pos[SSD_MAX_DRAFT + 1], next_tok[SSD_MAX_DRAFT + 1];
+};
+
+// ---- kernel classes for profiling
+enum KClass : int {
+    KC_ROWS = 0, KC_NORM, KC_GEMM_QKV, KC_ROPE, KC_ATTN, KC_GEMM_O, KC_GEMM_GU, KC_GEMM_DOWN,
+    KC_LMHEAD, KC_LMMERGE, KC_ACCEPT, KC_COUNT
+};
+
+struct Dims {
+    int L, d, Hq, Hkv, dh, F, V, mask_id, dtype;
+    float eps;
+    int max_seqs, max_seq_len, block, max_draft, max_rows;
+    int nq() const { return Hq * dh; }
+    int nkv() const { return Hkv * dh; }
+    int nqkv() const { return (Hq + 2 * Hkv) * dh; }
+    size_t esz() const { return dtype == SSD_F32 ? 4 : 2; }
+};
+
+// Workspace carve-up (all device pointers into the caller's workspace).
+struct Buffers {
+    float* h;            // [max_rows, d] residual stream, fp32
+    void* xn;            // [max_rows, d] normed rows, T
+    float* qkv;          // [max_rows, nqkv] fp32 projections before rotary embedding
+    void* q;             // [max_rows, nq] T, after rotary
+    void* k;             // [max_rows, nkv] T, after rotary (the node's own keys)
+    void* v;             // [max_rows, nkv] T
+    void* attn;          // [max_rows, nq] T
+    void* act;           // [max_rows, F] T
+    float* part;         // [SSD_MAX_SPLIT, max_rows, max(d, nqkv)] fp32 split-K partial sums
+    float* lm_part;      // [max_rows, n_vtiles, 3] (max, arg as float bits, sumexp)
+    float* row_max;      // [max_rows]
+    int* row_arg;        // [max_rows]
+    float* row_conf;     // [max_rows]
+    int* row_tok;        // [max_rows]
+    int* row_pos;        // [max_rows]
+    int* row_node;       // [max_rows]
+    int* raw_tok;        // [max_rows]
+    void* kcache;        // [L][max_seqs][Hkv][max_seq_len][dh] T
+    void* vcache;
+    float* rope_cos;     // [max_seq_len, dh/2]
+    float* rope_sin;
+    FwdHeader* fwd;      // device copy of the descriptor
+    SeqState* state;     // [max_seqs]
+    StepResult* result;  // [max_seqs]
+    int* out_tok;        // [max_seqs, max_seq_len] device token output of ssd_generate
+    int lm_tiles;        // vocab tiles of the LM-head reduction
+};
+
+struct LayerW {
+    const void *wqkv, *wo, *wgu, *wdown;
+    const float *norm1, *norm2;
+};
+
+struct ssd_ctx {
+    Dims dm;
+    Buffers b;
+    std::vector<LayerW> lw;
+    const void *embed, *lm_head;
+    const float* final_norm;
+    hipStream_t stream;
+    int kernel_path;
+    int cached_len[SSD_MAX_SEQS];
+    // host staging ring for descriptors / small uploads
+    static const int kSlots = 4;
+    char* stage[kSlots];
+    hipEvent_t stage_ev[kSlots];
+    bool stage_used[kSlots];
+    int stage_next;
+    size_t stage_bytes;
+    StepResult* host_result;   // pinned
+    // profiling
+    bool profiling;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<int> ev_class;
+    size_t ev_used;
+    double prof_ms[KC_COUNT];
+    long long prof_n[KC_COUNT];
+    std::string err;
+};
+
+// ---- launchers implemented in the kernel files (all asynchronous on `st`)
+// T-typed buffers are passed as void* with the dtype flag.
+void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes);
+void launch_embed(const ssd_ctx* c, int M, hipStream_t st);
+void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st);
+void launch_rope(const ssd_ctx* c, int M, int layer, hipStream_t st);
+void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
+void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st);
+void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);
+int lm_tiles_plain(int V);
+
+enum GemmEpi : int { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
+// out[M,N] = X[M,K] * W[N,K]^T with the plain FMA kernel.
+void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, void* out, int M, int N, int K,
+                       hipStream_t st);
+
+// MFMA path (bf16 only).  Return false if the shape is not supported.
+bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const void* W, void* out, int M, int N, int K,
+                      int* n_split, hipStream_t st);
+bool launch_attn_mfma(const ssd_ctx* c, int M, int layer, hipStream_t st);

@@ -1,0 +1,98 @@
+"""Helpers for the GPU-vs-oracle comparison protocol (teacher forced per forward).
+
+The oracle's trace gives, per forward: the block state, the drafts, and per node
+the predictions (t, m, c) and the top-2 logit margin.  The same state is fed to
+the HIP entry points and the outputs are compared row by row.
+
+Exemptions (counted and reported, never silent):
+  * token id: only where the oracle's top-2 logit margin is below `margin_tol`;
+  * acceptance decision: only where a compared token is exempt, or where the two
+    best position confidences of a walked node differ by less than `conf_tol`
+    in log space (a legitimate reordering of near-equal confidences).
+"""
+import math
+
+import numpy as np
+
+from oracle import decode
+
+
+def bits(masked):
+    return sum(1 << p for p, mk in enumerate(masked) if mk)
+
+
+def node_masks(masked, drafts):
+    out, mk = [list(masked)], list(masked)
+    for (q, _) in drafts:
+        mk[q] = False
+        out.append(list(mk))
+    return out
+
+
+def compare_record(rec, gpu, maxlogit_tol, margin_tol, conf_tol, conf_rtol):
+    """rec: oracle trace record; gpu: dict of host arrays for ONE sequence
+    (row_* of shape [max_draft+1, block], n_accept, acc_*, n_next, next_*).
+    Returns counters; raises AssertionError on a real mismatch."""
+    stats = dict(rows=0, tok_exempt=0, decision_exempt=0, max_dlogit=0.0)
+    masks = node_masks(rec["masked"], rec["drafts"])
+    n_nodes = len(masks)
+    B = len(rec["masked"])
+    tok_exempt_rows = set()
+    for j in range(n_nodes):
+        for p in range(B):
+            if not masks[j][p]:
+                continue
+            stats["rows"] += 1
+            dm = abs(float(gpu["row_maxlogit"][j, p]) - float(rec["m"][j][p]))
+            stats["max_dlogit"] = max(stats["max_dlogit"], dm)
+            assert dm <= maxlogit_tol, f"max-logit differs by {dm} at node {j} pos {p}"
+            if int(gpu["row_argmax"][j, p]) != int(rec["t"][j][p]):
+                assert float(rec["margin"][j][p]) < margin_tol, \
+                    f"arg-max differs at node {j} pos {p} with oracle margin {float(rec['margin'][j][p])}"
+                stats["tok_exempt"] += 1
+                tok_exempt_rows.add((j, p))
+            else:
+                co, cg = float(rec["c"][j][p]), float(gpu["row_conf"][j, p])
+                assert abs(cg - co) <= conf_rtol * co, f"confidence {cg} vs {co} at node {j} pos {p}"
+
+    # (1) the acceptance kernel must be exactly the chain walk applied to the GPU's own rows
+    n_next_cap = len(rec["next_drafts"]) if rec["next_drafts"] else 0
+    return stats, tok_exempt_rows, masks
+
+
+def expected_from_gpu_rows(rec, gpu, masks, n_draft_next):
+    """Chain walk (oracle's routine) applied to the GPU's own per-row outputs."""
+    import torch
+    n_nodes = len(masks)
+    t = [torch.tensor(gpu["row_argmax"][j]) for j in range(n_nodes)]
+    c = [torch.tensor(gpu["row_conf"][j]) for j in range(n_nodes)]
+    return decode.accept_chain(t, c, masks, rec["drafts"], n_draft_next)
+
+
+def decision_near_tie(rec, masks, conf_tol):
+    """True if any node the oracle walked has its two best masked confidences
+    within conf_tol in log space."""
+    m = len(rec["accepted"]) - 1
+    for j in range(m + 1):
+        cs = sorted((float(rec["c"][j][p]) for p, mk in enumerate(masks[j]) if mk), reverse=True)
+        if len(cs) >= 2 and math.log(cs[0]) - math.log(cs[1]) < conf_tol:
+            return True
+    # the ranking of the next drafts
+    cs = sorted((float(rec["c"][m][p]) for p, mk in enumerate(masks[m]) if mk), reverse=True)
+    return any(math.log(a) - math.log(b) < conf_tol for a, b in zip(cs, cs[1:]))
+
+
+def check_forward(rec, gpu, n_draft_next, maxlogit_tol, margin_tol, conf_tol, conf_rtol):
+    stats, tok_exempt_rows, masks = compare_record(rec, gpu, maxlogit_tol, margin_tol, conf_tol, conf_rtol)
+    acc, nxt, m = expected_from_gpu_rows(rec, gpu, masks, n_draft_next)
+    got_acc = [(int(gpu["acc_pos"][i]), int(gpu["acc_tok"][i])) for i in range(int(gpu["n_accept"]))]
+    got_nxt = [(int(gpu["next_pos"][i]), int(gpu["next_tok"][i])) for i in range(int(gpu["n_next"]))]
+    assert got_acc == acc, f"acceptance kernel {got_acc} != chain walk on its own rows {acc}"
+    assert got_nxt == nxt, f"next drafts {got_nxt} != ranking of its own rows {nxt}"
+    assert 1 <= len(got_acc) <= len(rec["drafts"]) + 1
+    # (2) against the oracle's decision
+    if got_acc != rec["accepted"] or got_nxt != rec["next_drafts"]:
+        assert tok_exempt_rows or decision_near_tie(rec, masks, conf_tol), \
+            f"decision differs from the oracle with no near-tie: {got_acc}/{got_nxt} vs {rec['accepted']}/{rec['next_drafts']}"
+        stats["decision_exempt"] += 1
+    return stats

@@ -1,0 +1,66 @@
+"""The C-ABI library loads and exports every symbol the public header declares.
+No compute calls here (runs without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssd_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_04147_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2510_04147_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2510_04147_amd import binding
+    syms = declared_symbols()
+    assert len(syms) >= 12
+    for s in syms:
+        assert hasattr(lib, s), f"{s} declared in include/ssd.h but not exported"
+    assert sorted(binding.EXPORTS) == syms
+
+
+def test_struct_layouts_match_header():
+    from paper_2510_04147_amd import binding
+    assert ctypes.sizeof(binding.SsdConfig) == 16 * 4
+    assert ctypes.sizeof(binding.SsdWeights) == 9 * 8
+    assert ctypes.sizeof(binding.SsdStepOut) == 9 * 8
+    assert ctypes.sizeof(binding.SsdStats) == 8 * (3 + 17 + 3)
+
+
+def test_config_validation_needs_no_gpu(lib):
+    from paper_2510_04147_amd import binding, synth
+    cfg = synth.model_config("tiny")
+    good = binding.make_config(cfg, 1, 256, 32, 4)
+    assert lib.ssd_workspace_bytes(ctypes.byref(good)) > 0
+    for field, value in [("block", 65), ("max_draft", 16), ("head_dim", 80), ("n_kv_heads", 3), ("dtype", 7),
+                         ("mask_id", 5000), ("max_seqs", 17), ("d_model", 250)]:
+        bad = binding.make_config(cfg, 1, 256, 32, 4)
+        setattr(bad, field, value)
+        bad.max_rows = 1 << 20
+        assert lib.ssd_workspace_bytes(ctypes.byref(bad)) == 0, field
+    small = binding.make_config(cfg, 2, 256, 32, 4)
+    small.max_rows = 100                      # < max_seqs*(max_draft+1)*block
+    assert lib.ssd_workspace_bytes(ctypes.byref(small)) == 0
+    # ssd_create rejects a bad config before touching the device
+    h = ctypes.c_void_p()
+    bad = binding.make_config(cfg, 1, 256, 65, 4)
+    w = binding.SsdWeights()
+    rc = lib.ssd_create(ctypes.byref(bad), ctypes.byref(w), ctypes.c_void_p(256), 1 << 30, None, ctypes.byref(h))
+    assert rc == -2 and lib.ssd_strerror(rc) == b"size or index out of range for this context"
+    rc = lib.ssd_create(ctypes.byref(good), ctypes.byref(w), ctypes.c_void_p(256), 1 << 30, None, ctypes.byref(h))
+    assert rc == -1                            # null weight pointers
+    assert lib.ssd_destroy(None) == -1

@@ -1,0 +1,195 @@
+"""GPU parity on the tiny fp32 configuration (2 layers, d=256, vocab 1024):
+teacher-forced forwards against the fp64 oracle, SSD == stepwise on the GPU bit
+for bit, the zero-attention closed form, and error handling."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decode
+from paper_2510_04147_amd import synth
+from parity_util import bits, check_forward
+
+pytestmark = pytest.mark.gpu
+
+# fp32 kernels against the fp64 oracle: tolerances of the tiny configuration
+MAXLOGIT_TOL = 1e-4
+MARGIN_TOL = 1e-2
+CONF_TOL = 1e-3       # log-space gap below which two position confidences count as tied
+CONF_RTOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def setup():
+    from paper_2510_04147_amd import binding
+    cfg = synth.model_config("tiny")
+    w = synth.gen_weights(cfg, 0)
+    wg = synth.weights_to(w, "cuda")
+    eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=32, max_draft=8, max_rows=2 * 9 * 32)
+    yield cfg, w, wg, eng
+    eng.close()
+
+
+def teacher_forced(eng, cfg, w, prompt, gen_len, block, N, **tol):
+    trace = []
+    ref, st = decode.ssd(w, cfg, prompt, gen_len, block, N, trace=trace)
+    eng.reset(0)
+    eng.prefill_kv(0, prompt, 0)
+    out = eng.new_out(1)
+    totals = dict(rows=0, tok_exempt=0, decision_exempt=0, max_dlogit=0.0, forwards=0)
+    P = len(prompt)
+    for i, rec in enumerate(trace):
+        print(f"forward {i}: S={rec['S']} drafts={len(rec['drafts'])}", flush=True)
+        if eng.cached_len(0) < rec["S"]:          # previous block finished: append its (oracle) tokens
+            lo = eng.cached_len(0) - P
+            eng.prefill_kv(0, ref[lo:rec["S"] - P], eng.cached_len(0))
+        bl = len(rec["tok"])
+        eng.verify_tree([0], [rec["tok"]], [bits(rec["masked"])], [rec["S"]], [rec["drafts"]], N, out, block_len=[bl])
+        g = {k: v[0] for k, v in out.host().items()}
+        s = check_forward(rec, g, N, **tol)
+        for k in ("rows", "tok_exempt", "decision_exempt"):
+            totals[k] += s[k]
+        totals["max_dlogit"] = max(totals["max_dlogit"], s["max_dlogit"])
+        totals["forwards"] += 1
+    return ref, st, totals
+
+
+def test_teacher_forced_verify_matches_oracle(setup):
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 1001, 64)
+    ref, st, tot = teacher_forced(eng, cfg, w, prompt, 64, 32, 4, maxlogit_tol=MAXLOGIT_TOL, margin_tol=MARGIN_TOL,
+                                  conf_tol=CONF_TOL, conf_rtol=CONF_RTOL)
+    print("teacher-forced totals:", tot)
+    assert tot["forwards"] == st["forwards"] and tot["rows"] > 1000
+    assert tot["tok_exempt"] <= 0.02 * tot["rows"] and tot["decision_exempt"] <= 2
+
+
+def test_teacher_forced_ragged_block_and_deep_tree(setup):
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 7, 37)
+    ref, st, tot = teacher_forced(eng, cfg, w, prompt, 45, 32, 8, maxlogit_tol=MAXLOGIT_TOL, margin_tol=MARGIN_TOL,
+                                  conf_tol=CONF_TOL, conf_rtol=CONF_RTOL)
+    assert tot["forwards"] == st["forwards"]
+
+
+def exempt_or_equal(cfg, w, prompt, gen_len, block, got, dtype=torch.float64):
+    """Free-running comparison: equal to the oracle, or the first divergence sits
+    on a decision the oracle itself marks as a near-tie."""
+    trace = []
+    ref, _ = decode.stepwise(w, cfg, prompt, gen_len, block, dtype=dtype, trace=trace)
+    if list(got) == ref:
+        return 0
+    P = len(prompt)
+    for rec in trace:
+        (p, t), = rec["accepted"]
+        if int(got[rec["S"] - P + p]) != t:
+            cs = sorted((float(rec["c"][0][q]) for q, mk in enumerate(rec["masked"]) if mk), reverse=True)
+            near = float(rec["margin"][0][p]) < MARGIN_TOL or \
+                (len(cs) > 1 and math.log(cs[0]) - math.log(cs[1]) < CONF_TOL)
+            assert near, f"tokens diverge from the oracle at S={rec['S']} pos {p} without a near-tie"
+            return 1
+    return 1
+
+
+def test_generate_ssd_equals_stepwise_and_oracle(setup):
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 1001, 64)
+    base, st0 = eng.generate([prompt], 64, 32, 0)
+    assert st0["forwards"] == 64 and st0["tokens"] == 64 and st0["accept_hist"][1] == 64
+    exempt_or_equal(cfg, w, prompt, 64, 32, base[0])
+    for N in range(1, 9):
+        out, st = eng.generate([prompt], 64, 32, N)
+        assert np.array_equal(out, base), f"GPU SSD (N={N}) differs from GPU stepwise"
+        assert st["tokens"] == 64 and st["forwards"] <= 64
+        assert all(h == 0 for a, h in enumerate(st["accept_hist"]) if a > N + 1 or a == 0)
+        assert 1.0 - st["forwards"] / 64 <= N / (N + 1) + 1e-12
+    _, so = decode.ssd(w, cfg, prompt, 64, 32, 4)
+    _, sg = eng.generate([prompt], 64, 32, 4)
+    print("forwards oracle/gpu:", so["forwards"], sg["forwards"], sg["accept_hist"][:6])
+
+
+def test_generate_batch_of_two_ragged(setup):
+    cfg, w, wg, eng = setup
+    p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)
+    both, st = eng.generate([p0, p1], 40, 16, 3)
+    a, _ = eng.generate([p0], 40, 16, 0)
+    b, _ = eng.generate([p1], 40, 16, 0)
+    assert np.array_equal(both[0], a[0]) and np.array_equal(both[1], b[0])
+    assert st["tokens"] == 80
+    exempt_or_equal(cfg, w, p1, 40, 16, both[1])
+
+
+def test_zero_attention_closed_form_on_gpu(setup):
+    from paper_2510_04147_amd import binding
+    cfg, w, _, _ = setup
+    w0 = dict(w)
+    w0["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w["layers"]]
+    eng = binding.SSD(cfg, synth.weights_to(w0, "cuda"), max_seqs=1, max_seq_len=256, block=32, max_draft=8)
+    prompt = synth.gen_prompt(cfg, 3, 20)
+    ref, _ = decode.stepwise(w0, cfg, prompt, 64, 32)
+    for N in (0, 1, 4, 5, 8):
+        out, st = eng.generate([prompt], 64, 32, N)
+        assert list(out[0]) == ref and len(set(out[0])) == 1
+        assert st["forwards"] == 2 * (1 + math.ceil(31 / (N + 1))), (N, st)
+    eng.close()
+
+
+def test_repeated_forward_is_bit_identical_and_node_independent(setup):
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 5, 40)
+    eng.reset(0)
+    eng.prefill_kv(0, prompt, 0)
+    tok = [cfg["mask_id"]] * 32
+    tok[3], tok[9] = 17, 400
+    masked = [True] * 32
+    masked[3] = masked[9] = False
+    drafts = [(5, 11), (0, 12), (30, 13)]
+    o1, o2, o3 = eng.new_out(1), eng.new_out(1), eng.new_out(1)
+    eng.verify_tree([0], [tok], [bits(masked)], [40], [drafts], 4, o1)
+    eng.verify_tree([0], [tok], [bits(masked)], [40], [drafts], 4, o2)
+    a, b = o1.host(), o2.host()
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    # node 2 of the chain == a stand-alone one-node forward on that state
+    t2, m2 = list(tok), list(masked)
+    for q, d in drafts[:2]:
+        t2[q], m2[q] = d, False
+    eng.draft([0], [t2], [bits(m2)], [40], 4, o3)
+    c = o3.host()
+    sel = np.array(m2)
+    for k in ("row_maxlogit", "row_argmax", "row_conf"):
+        assert np.array_equal(a[k][0, 2][sel], c[k][0, 0][sel]), k
+
+
+def test_error_codes(setup):
+    from paper_2510_04147_amd.binding import SsdError
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 5, 40)
+    eng.reset(0)
+    eng.prefill_kv(0, prompt, 0)
+    out = eng.new_out(1)
+    tok, full = [cfg["mask_id"]] * 32, (1 << 32) - 1
+
+    def code(fn):
+        with pytest.raises(SsdError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: eng.prefill_kv(0, prompt, 41)) == -5            # beyond the cached prefix
+    assert code(lambda: eng.prefill_kv(0, [1] * 250, 40)) == -2         # pos0+n > max_seq_len
+    assert code(lambda: eng.prefill_kv(0, [5000], 40)) == -2            # token id out of range
+    assert code(lambda: eng.prefill_kv(9, [1], 0)) == -2                # bad slot
+    assert code(lambda: eng.verify_tree([0], [tok], [full], [39], [[]], 4, out)) == -5
+    assert code(lambda: eng.verify_tree([0], [tok], [full], [40], [[(40, 1)]], 4, out)) == -1   # not a block position
+    assert code(lambda: eng.verify_tree([0], [tok], [full & ~2], [40], [[(1, 7)]], 4, out)) == -1  # not masked
+    assert code(lambda: eng.verify_tree([0], [tok], [full], [40], [[(1, 7), (1, 8)]], 4, out)) == -1  # duplicate
+    assert code(lambda: eng.verify_tree([0], [tok], [full], [40], [[(i, 7) for i in range(9)]], 4, out)) == -2
+    assert code(lambda: eng.verify_tree([0], [tok], [0b11], [40], [[(0, 7), (1, 8)]], 4, out)) == -1  # leaf left empty
+    assert code(lambda: eng.verify_tree([0, 0], [tok, tok], [full, full], [40, 40], [[], []], 4, out)) == -1
+    assert code(lambda: eng.verify_tree([0], [tok], [0], [40], [[]], 4, out)) == -1
+    assert code(lambda: eng.generate([prompt], 300, 32, 4)) == -2
+    assert code(lambda: eng.generate([prompt], 64, 33, 4)) == -2
+    # the context still works after rejected calls
+    eng.verify_tree([0], [tok], [full], [40], [[]], 4, out)
+    assert int(out.host()["n_accept"][0]) == 1

@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD hot path on one MI355X.
+
+A "step" is one pass of the whole hot path: one batched verification forward
+(tree build, embedding, all layers, LM-head reduction, acceptance) of the
+8B-class workload (prompt 256, block 32, draft depth 4 -> 5 nodes, M = 160 rows)
+against a cached prefix of S = 384 positions (the middle of the 256..480 range
+the workload sweeps).  Inputs, weights and the prefix KV are resident in HBM
+before the timed region.
+
+Prints ONE JSON line.  `value` is generated tokens/s of a complete
+ssd_generate run of the same workload (prompt prefill and KV-append passes
+included); `ms_per_step` is the verification-forward latency of the K timed
+steps; `roofline` covers the dominant kernel (the gate/up projection GEMM)
+with HIP-event timing on the library's stream; `forward` gives the whole
+forward against the HBM roofline; `cpu_baseline` times the CPU oracle on a
+bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2_8b_b32_n4")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; marks the line invalid)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-generate", action="store_true")
+    ap.add_argument("--prefix", type=int, default=384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_04147_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    over = {"n_layers": args.layers} if args.layers else {}
+    cfg = synth.model_config(wl["model"], **over)
+    B, N, P, G = wl["block"], wl["draft"], wl["prompt_len"], wl["gen_len"]
+    assert wl["batch"] == 1, "the bench line is the batch-1 workload"
+    def note(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    note(f"generating weights for {args.workload} ({cfg['n_layers']} layers)")
+    wg = synth.gen_weights(cfg, 0, device="cuda")
+    torch.cuda.synchronize()                 # the library reads the weights on its own stream
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=P + G, block=B, max_draft=N, max_rows=max(P, args.prefix, (N + 1) * B))
+        # ---- verification forward at prefix S, fixed block state with N drafts
+        S = args.prefix
+        note(f"context created; prefill of {S} positions")
+        prefix = synth.gen_prompt(cfg, wl["seed"], S)
+        eng.prefill_kv(0, prefix, 0)
+        tok = [cfg["mask_id"]] * B
+        masked = (1 << B) - 1
+        drafts = [(3 + 5 * i, 100 + i) for i in range(N)]
+        out = eng.new_out(1)
+
+        def step():
+            eng.verify_tree([0], [tok], [masked], [S], [drafts], N, out)
+
+        stream.synchronize()
+        note("warm-up verification forwards")
+        for _ in range(args.warmup):
+            step()
+        stream.synchronize()
+        note(f"timing {args.steps} verification forwards")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(args.steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_step = e0.elapsed_time(e1) / args.steps
+
+        # ---- per-kernel-class timing (HIP events on the same stream, separate pass)
+        note(f"{ms_step:.3f} ms per forward; per-kernel event timing")
+        eng.profile_begin()
+        for _ in range(max(3, args.steps // 5)):
+            step()
+        prof = eng.profile_read()
+        eng.profile_end()
+        n_prof = max(3, args.steps // 5)
+
+        # ---- whole generation of the workload: SSD and stepwise
+        gen = {}
+        if not args.no_generate:
+            note("full generation: SSD, then stepwise")
+            prompt = synth.gen_prompt(cfg, wl["seed"], P)
+            eng.generate([prompt], B, B, N)                      # warm
+            toks_ssd, st_ssd = eng.generate([prompt], G, B, N)
+            toks_step, st_step = eng.generate([prompt], G, B, 0)
+            same = bool(np.array_equal(toks_ssd, toks_step))
+            gen = dict(
+                ssd_tokens_per_s=G / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=G / (st_step["total_ms"] / 1e3),
+                ssd_forwards=st_ssd["forwards"], stepwise_forwards=st_step["forwards"], kv_passes=st_ssd["kv_passes"],
+                accepted_per_forward=G / st_ssd["forwards"], accept_hist=st_ssd["accept_hist"][:N + 2],
+                ssd_decode_ms_per_forward=st_ssd["decode_ms"] / st_ssd["forwards"],
+                stepwise_ms_per_forward=st_step["decode_ms"] / st_step["forwards"],
+                ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"])
+
+    # ---- roofline arithmetic
+    M = (N + 1) * B
+    params = synth.streamed_param_count(cfg)
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    bytes_fwd = params * esz + S * synth.kv_bytes_per_token(cfg)
+    fwd_gbs = bytes_fwd / (ms_step * 1e-3) / 1e9
+    d, F = cfg["d_model"], cfg["d_ffn"]
+    gu = prof.get("gemm_gate_up_swiglu", dict(launches=0, ms=0.0))
+    gu_bytes = 2 * F * d * esz + M * d * esz + M * F * esz     # weights + activations in + SwiGLU out
+    gu_us = 1e3 * gu["ms"] / max(gu["launches"], 1)
+    gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9 if gu_us > 0 else 0.0
+    line = {
+        "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
+        "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "model": wl["model"], "n_layers": cfg["n_layers"], "batch": 1,
+                   "prompt_len": P, "gen_len": G, "block": B, "draft_depth": N, "rows_per_forward": M,
+                   "prefix_len_timed": S},
+        "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"]},
+        "forward": {"bytes_per_forward": bytes_fwd, "achieved_GBs": fwd_gbs, "frac_of_hbm_peak": fwd_gbs / HBM_PEAK_GBS,
+                    "host_wall_ms_per_step": wall_ms,
+                    "kernel_classes_us_per_forward": {k: 1e3 * v["ms"] / n_prof for k, v in prof.items()}},
+        "generate": gen,
+    }
+    if args.layers:
+        line["invalid"] = "layer count overridden"
+
+    # ---- CPU oracle on a bounded sample (reported baseline, never a target)
+    if not args.no_cpu_baseline:
+        from oracle import decode
+        note("CPU oracle sample")
+        w = synth.weights_to(wg, "cpu")
+        del wg
+        torch.cuda.empty_cache()
+        n_pre, nb = 16, 4                      # 16-token prefix, one 4-position block, stepwise
+        sample_prompt = synth.gen_prompt(cfg, wl["seed"], n_pre)
+        t0 = time.perf_counter()
+        toks, st = decode.stepwise(w, cfg, sample_prompt, nb, nb, dtype=torch.float32)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": nb / dt, "unit": "tokens/s", "cores": torch.get_num_threads(),
+                                "kind": "oracle", "seconds": dt,
+                                "sample": f"oracle stepwise decoding (fp32 activations, bf16 weights upcast per use) "
+                                          f"on the same {cfg['n_layers']}-layer model: {n_pre}-token prefill, one "
+                                          f"{nb}-position block = {st['forwards']} forwards + {st['kv_passes']} KV passes"}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -122,6 +122,8 @@ size_t ssd_workspace_bytes(const ssd_config* cfg);
 
 /* Create a context.  `workspace` is device memory of at least ssd_workspace_bytes(cfg),
  * 256-byte aligned; `hip_stream` is a hipStream_t (NULL = the default stream).
+ * The weights must be completely written before the call: bf16 weights are
+ * repacked into the workspace by kernels on `hip_stream`.
  * Errors: SSD_EINVAL (null / inconsistent config), SSD_ERANGE (block, draft or
  * head_dim beyond the supported limits), SSD_ENOMEM, SSD_EHIP. */
 int ssd_create(const ssd_config* cfg, const ssd_weights* weights, void* workspace,

@@ -11,12 +11,27 @@ segment never change and can be cached exactly.
 Every formula is written out; torch is used for matmul, exp, sqrt, cos, sin.
 Weights arrive as [out_features, in_features] tensors (fp32 or bf16) and are
 upcast to the compute dtype at the point of use.
+
+Operand precision.  cfg["operand_dtype"] (absent/None = exact) names the
+storage type of matrix-multiply operands in the bf16 configurations: every
+activation that enters a matrix product (normed rows, rotated q and k, v,
+softmax probabilities, attention output, SwiGLU output) is rounded to that
+type first, then the product, the softmax, the norms and the residual stream
+are evaluated in the compute dtype.  With operand_dtype=None nothing is
+rounded: that is the reference the deviation of a bf16 pipeline is reported
+against.
 """
 from __future__ import annotations
 
 import math
 
 import torch
+
+
+def _operand(x, cfg):
+    """Round an activation to the operand storage type of the configuration."""
+    od = cfg.get("operand_dtype")
+    return x if od is None else x.to(od).to(x.dtype)
 
 
 def rms_norm(x, g, eps):
@@ -43,7 +58,7 @@ def silu(x):
     return x / (1.0 + torch.exp(-x))
 
 
-def attention(q, k, v, allowed=None):
+def attention(q, k, v, allowed=None, cfg=None):
     """softmax(q k^T / sqrt(dh)) v per head.
     q: [n, Hq, dh]; k, v: [m, Hkv, dh]; query head h reads kv head h // (Hq/Hkv).
     allowed: optional [n, m] bool (True = may attend).  Returns [n, Hq, dh]."""
@@ -59,6 +74,8 @@ def attention(q, k, v, allowed=None):
         s = s - s.max(dim=-1, keepdim=True).values
         p = torch.exp(s)
         p = p / p.sum(dim=-1, keepdim=True)
+        if cfg is not None:
+            p = _operand(p, cfg)
         out[:, h, :] = p @ vh
     return out
 
@@ -84,20 +101,21 @@ def _layer(h, lw, cfg, pos, k_prefix, v_prefix, allowed, dtype):
     Hq, Hkv, dh = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
     F = cfg["d_ffn"]
     n = h.shape[0]
-    x = rms_norm(h, lw["norm1"], cfg["rms_eps"])
+    x = _operand(rms_norm(h, lw["norm1"], cfg["rms_eps"]), cfg)
     qkv = x @ lw["wqkv"].to(dtype).T
     q = qkv[:, : Hq * dh].reshape(n, Hq, dh)
     k = qkv[:, Hq * dh: (Hq + Hkv) * dh].reshape(n, Hkv, dh)
     v = qkv[:, (Hq + Hkv) * dh:].reshape(n, Hkv, dh)
-    q = rope(q, pos, cfg["rope_theta"])
-    k = rope(k, pos, cfg["rope_theta"])
+    q = _operand(rope(q, pos, cfg["rope_theta"]), cfg)
+    k = _operand(rope(k, pos, cfg["rope_theta"]), cfg)
+    v = _operand(v, cfg)
     k_all = k if k_prefix is None else torch.cat([k_prefix, k], 0)
     v_all = v if v_prefix is None else torch.cat([v_prefix, v], 0)
-    a = attention(q, k_all, v_all, allowed).reshape(n, Hq * dh)
+    a = _operand(attention(q, k_all, v_all, allowed, cfg).reshape(n, Hq * dh), cfg)
     h = h + a @ lw["wo"].to(dtype).T
-    x = rms_norm(h, lw["norm2"], cfg["rms_eps"])
+    x = _operand(rms_norm(h, lw["norm2"], cfg["rms_eps"]), cfg)
     gu = x @ lw["wgu"].to(dtype).T
-    h = h + (silu(gu[:, :F]) * gu[:, F:]) @ lw["wdown"].to(dtype).T
+    h = h + _operand(silu(gu[:, :F]) * gu[:, F:], cfg) @ lw["wdown"].to(dtype).T
     return h, k, v
 
 
@@ -117,7 +135,7 @@ def forward_segment(w, cfg, tokens, pos0, cache, dtype=torch.float64, need_logit
         new_kv.append((k, v))
     if not need_logits:
         return None, new_kv
-    hn = rms_norm(h, w["final_norm"], cfg["rms_eps"])
+    hn = _operand(rms_norm(h, w["final_norm"], cfg["rms_eps"]), cfg)
     return hn @ w["lm_head"].to(dtype).T, new_kv
 
 
@@ -132,5 +150,5 @@ def forward_full_blockcausal(w, cfg, tokens, seg, dtype=torch.float64):
     h = w["embed"][tokens].to(dtype)
     for lw in w["layers"]:
         h, _, _ = _layer(h, lw, cfg, pos, None, None, allowed, dtype)
-    hn = rms_norm(h, w["final_norm"], cfg["rms_eps"])
+    hn = _operand(rms_norm(h, w["final_norm"], cfg["rms_eps"]), cfg)
     return hn @ w["lm_head"].to(dtype).T

@@ -163,6 +163,9 @@ class SSD:
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = (self.workspace.data_ptr() + 255) & ~255
         self.stream = torch.cuda.current_stream(dev)
+        # ssd_create reads the weights on this stream (it repacks them): whatever produced
+        # them, on any stream, must have finished
+        torch.cuda.synchronize(dev)
         h = C.c_void_p()
         rc = self.lib.ssd_create(C.byref(self.ccfg), C.byref(w), C.c_void_p(base), C.c_size_t(nbytes),
                                  C.c_void_p(self.stream.cuda_stream), C.byref(h))

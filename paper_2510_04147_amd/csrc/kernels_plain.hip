@@ -75,9 +75,13 @@ __global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restr
 
 // a1: embedding gather into the fp32 residual stream.
 template <typename T>
-__global__ void k_embed(const T* __restrict__ embed, const int* __restrict__ row_tok, float* __restrict__ h, int d) {
+__global__ void k_embed(const T* __restrict__ embed, const int* __restrict__ row_tok, float* __restrict__ h, int d,
+                        int V) {
     const int row = blockIdx.x;
-    const T* e = embed + (size_t)row_tok[row] * d;
+    // ids are validated on the host or produced by the arg-max; the clamp keeps the gather in
+    // bounds whatever a corrupted state holds
+    const int tok = min(max(row_tok[row], 0), V - 1);
+    const T* e = embed + (size_t)tok * d;
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)row * d + i] = ld_f(e + i);
 }
 
@@ -108,22 +112,30 @@ __global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float
 // conversion to the operand type, and the cache write for nodes that own
 // finished tokens.
 template <typename T>
-__global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ qkv,
-                                              const int* __restrict__ row_pos, const int* __restrict__ row_node,
+__global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ part,
+                                              int n_part, size_t part_stride, const int* __restrict__ row_pos, const int* __restrict__ row_node,
                                               const float* __restrict__ cosT, const float* __restrict__ sinT,
                                               T* __restrict__ q, T* __restrict__ k, T* __restrict__ v,
+                                              T* __restrict__ vt, int vt_rows,
                                               T* __restrict__ kcache, T* __restrict__ vcache, int Hq, int Hkv,
-                                              int dh, int layer, int max_seqs, int max_seq_len) {
+                                              int dh, int layer, int max_seqs, int seq_stride) {
     const int row = blockIdx.x;
     const int pos = row_pos[row];
     const NodeDesc nd = fw->nodes[row_node[row]];
     const int half = dh >> 1;
     const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
-    const float* src = qkv + (size_t)row * nqkv;
-    const size_t cbase = (((size_t)layer * max_seqs + nd.seq) * Hkv) * (size_t)max_seq_len * dh;
+    const float* src = part + (size_t)row * nqkv;
+    // sum of the projection's split-K partial sums, in split order
+    auto val = [&](int col) {
+        float v = src[col];
+        for (int s = 1; s < n_part; ++s) v += src[s * part_stride + col];
+        return v;
+    };
+    const size_t cbase = (((size_t)layer * max_seqs + nd.seq) * Hkv) * (size_t)seq_stride * dh;
+    const int vrow = nd.vrow0 + (row - nd.row0);
     for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += 256) {
         const int head = idx / half, i = idx - head * half;
-        const float x1 = src[head * dh + i], x2 = src[head * dh + i + half];
+        const float x1 = val(head * dh + i), x2 = val(head * dh + i + half);
         const float c = cosT[(size_t)pos * half + i], s = sinT[(size_t)pos * half + i];
         const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
         if (head < Hq) {
@@ -134,19 +146,17 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
             st_f(k + (size_t)row * nkv + kh * dh + i, o1);
             st_f(k + (size_t)row * nkv + kh * dh + i + half, o2);
             if (nd.write_kv) {
-                T* dst = kcache + cbase + ((size_t)kh * max_seq_len + pos) * dh;
+                T* dst = kcache + cbase + ((size_t)kh * seq_stride + pos) * dh;
                 st_f(dst + i, o1);
                 st_f(dst + i + half, o2);
             }
         }
     }
     for (int idx = threadIdx.x; idx < nkv; idx += 256) {
-        const float x = src[nq + nkv + idx];
+        const float x = val(nq + nkv + idx);
         st_f(v + (size_t)row * nkv + idx, x);
-        if (nd.write_kv) {
-            const int kh = idx / dh, i = idx - kh * dh;
-            st_f(vcache + cbase + ((size_t)kh * max_seq_len + pos) * dh + i, x);
-        }
+        st_f(vt + (size_t)idx * vt_rows + vrow, x);
+        if (nd.write_kv) st_f(vcache + cbase + (size_t)idx * seq_stride + pos, x);
     }
 }
 
@@ -158,7 +168,7 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
                                                    const T* __restrict__ q, const T* __restrict__ k,
                                                    const T* __restrict__ v, const T* __restrict__ kcache,
                                                    const T* __restrict__ vcache, T* __restrict__ out, int Hq,
-                                                   int Hkv, int dh, int layer, int max_seqs, int max_seq_len) {
+                                                   int Hkv, int dh, int layer, int max_seqs, int seq_stride) {
     const int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     const NodeDesc nd = fw->nodes[row_node[row]];
     const int kvh = head / (Hq / Hkv);
@@ -166,7 +176,7 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
     __shared__ float qs[128];
     for (int i = lane; i < dh; i += 64) qs[i] = ld_f(q + (size_t)row * nq + head * dh + i);
     __syncthreads();
-    const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)max_seq_len * dh;
+    const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)seq_stride * dh;
     const T* kc = kcache + cbase;
     const T* vc = vcache + cbase;
     const T* kown = k + (size_t)nd.row0 * nkv + kvh * dh;
@@ -193,9 +203,12 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
         for (int jj = 0; jj < cnt; ++jj) {
             const float pj = __shfl(p, jj, 64);
             const int jk = t0 + jj;
-            const T* vp = jk < nd.S ? vc + (size_t)jk * dh : vown + (size_t)(jk - nd.S) * nkv;
-            o0 += pj * ld_f(vp + lane);
-            if (dh > 64) o1 += pj * ld_f(vp + lane + 64);
+            // cached values are stored position-contiguous: element (pos, i) at [i * seq_stride + pos]
+            const bool pre = jk < nd.S;
+            const T* vp = pre ? vc + jk : vown + (size_t)(jk - nd.S) * nkv;
+            const size_t es = pre ? (size_t)seq_stride : 1;
+            o0 += pj * ld_f(vp + lane * es);
+            if (dh > 64) o1 += pj * ld_f(vp + (lane + 64) * es);
         }
         m = m_new;
     }
@@ -329,7 +342,7 @@ __device__ __forceinline__ void lm_fold(float& m, int& a, float& s, float om, in
 
 __global__ __launch_bounds__(64) void k_lm_merge(const float* __restrict__ part, int n_tiles,
                                                  float* __restrict__ row_max, int* __restrict__ row_arg,
-                                                 float* __restrict__ row_conf) {
+                                                 float* __restrict__ row_conf, int V, int mask_id) {
     const int row = blockIdx.x, lane = threadIdx.x;
     float m = -INFINITY, s = 0.f;
     int a = 0x7fffffff;
@@ -352,9 +365,14 @@ __global__ __launch_bounds__(64) void k_lm_merge(const float* __restrict__ part,
         }
     }
     if (lane == 0) {
+        // Non-finite logits (NaN weights) leave no arg-max: fall back to the lowest valid id and
+        // confidence 0 so that every later step stays well defined and in bounds.
+        if ((unsigned)a >= (unsigned)V) a = mask_id == 0 ? 1 : 0;
+        float conf = 1.0f / s;             // softmax probability of the arg-max (Section 3.2.2)
+        if (!(conf >= 0.f && conf <= 1.f)) conf = 0.f;
         row_max[row] = m;
         row_arg[row] = a;
-        row_conf[row] = 1.0f / s;          // softmax probability of the arg-max (Section 3.2.2)
+        row_conf[row] = conf;
     }
 }
 
@@ -463,13 +481,13 @@ void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes) {
 
 void launch_embed(const ssd_ctx* c, int M, hipStream_t st) {
     if (c->dm.dtype == SSD_F32)
-        k_embed<float><<<M, 256, 0, st>>>((const float*)c->embed, c->b.row_tok, c->b.h, c->dm.d);
+        k_embed<float><<<M, 256, 0, st>>>((const float*)c->embed, c->b.row_tok, c->b.h, c->dm.d, c->dm.V);
     else
-        k_embed<bf16_t><<<M, 256, 0, st>>>((const bf16_t*)c->embed, c->b.row_tok, c->b.h, c->dm.d);
+        k_embed<bf16_t><<<M, 256, 0, st>>>((const bf16_t*)c->embed, c->b.row_tok, c->b.h, c->dm.d, c->dm.V);
 }
 
 void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st) {
-    const size_t stride = (size_t)c->dm.max_rows * c->dm.d;
+    const size_t stride = (size_t)c->dm.max_rows * c->part_cols;
     if (c->dm.dtype == SSD_F32)
         k_norm<float><<<M, 256, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (float*)c->b.xn, c->dm.d, c->dm.eps);
     else
@@ -477,18 +495,21 @@ void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStre
                                           c->dm.eps);
 }
 
-void launch_rope(const ssd_ctx* c, int M, int layer, hipStream_t st) {
+void launch_rope(const ssd_ctx* c, int M, int layer, int n_part, hipStream_t st) {
     const Dims& d = c->dm;
+    const size_t ps = (size_t)d.max_rows * c->part_cols;
     if (d.dtype == SSD_F32)
-        k_rope<float><<<M, 256, 0, st>>>(c->b.fwd, c->b.qkv, c->b.row_pos, c->b.row_node, c->b.rope_cos,
+        k_rope<float><<<M, 256, 0, st>>>(c->b.fwd, c->b.part, n_part, ps, c->b.row_pos, c->b.row_node, c->b.rope_cos,
                                          c->b.rope_sin, (float*)c->b.q, (float*)c->b.k, (float*)c->b.v,
+                                         (float*)c->b.vt, d.vt_rows(),
                                          (float*)c->b.kcache, (float*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
-                                         d.max_seqs, d.max_seq_len);
+                                         d.max_seqs, d.seq_stride());
     else
-        k_rope<bf16_t><<<M, 256, 0, st>>>(c->b.fwd, c->b.qkv, c->b.row_pos, c->b.row_node, c->b.rope_cos,
+        k_rope<bf16_t><<<M, 256, 0, st>>>(c->b.fwd, c->b.part, n_part, ps, c->b.row_pos, c->b.row_node, c->b.rope_cos,
                                           c->b.rope_sin, (bf16_t*)c->b.q, (bf16_t*)c->b.k, (bf16_t*)c->b.v,
+                                          (bf16_t*)c->b.vt, d.vt_rows(),
                                           (bf16_t*)c->b.kcache, (bf16_t*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
-                                          d.max_seqs, d.max_seq_len);
+                                          d.max_seqs, d.seq_stride());
 }
 
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st) {
@@ -498,13 +519,13 @@ void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st) {
         k_attn_plain<float><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const float*)c->b.q, (const float*)c->b.k,
                                                  (const float*)c->b.v, (const float*)c->b.kcache,
                                                  (const float*)c->b.vcache, (float*)c->b.attn, d.Hq, d.Hkv, d.dh,
-                                                 layer, d.max_seqs, d.max_seq_len);
+                                                 layer, d.max_seqs, d.seq_stride());
     else
         k_attn_plain<bf16_t><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const bf16_t*)c->b.q,
                                                   (const bf16_t*)c->b.k, (const bf16_t*)c->b.v,
                                                   (const bf16_t*)c->b.kcache, (const bf16_t*)c->b.vcache,
                                                   (bf16_t*)c->b.attn, d.Hq, d.Hkv, d.dh, layer, d.max_seqs,
-                                                  d.max_seq_len);
+                                                  d.seq_stride());
 }
 
 template <typename T>
@@ -530,7 +551,8 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
 int lm_tiles_plain(int V) { return (V + PBN - 1) / PBN; }
 
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
-    k_lm_merge<<<M, 64, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf);
+    k_lm_merge<<<M, 64, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf, c->dm.V,
+                                 c->dm.mask_id);
 }
 
 void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st) {

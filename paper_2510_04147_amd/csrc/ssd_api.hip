@@ -2,6 +2,7 @@
 // (one pass of the transformer over a list of node groups) and the decoding
 // loop of Algorithm 1.  All arithmetic of the method runs in the kernels; the
 // host only decides which forward to launch next.
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -77,8 +78,17 @@ static Dims dims_of(const ssd_config* c) {
     return d;
 }
 
-// the plain kernel has the finest vocabulary tiling, so its tile count bounds every path's
-static int lm_tiles_for(const Dims& d) { return lm_tiles_plain(d.V); }
+// the finest vocabulary tiling of any kernel path is 32 columns per partial
+static int lm_tiles_for(const Dims& d) { return (d.V + 31) / 32; }
+
+static bool packable(const Dims& d, size_t N, size_t K) { return d.dtype == SSD_BF16 && N % 32 == 0 && K % 16 == 0; }
+
+// Bytes of the fragment-order weight copies (bf16 models; shapes that do not tile stay unpacked).
+static size_t packed_bytes(const Dims& d) {
+    if (d.dtype != SSD_BF16) return 0;
+    auto sz = [&](size_t N, size_t K) { return packable(d, N, K) ? ((N * K * 2 + 255) & ~(size_t)255) : 0; };
+    return (sz(d.nqkv(), d.d) + sz(d.d, d.nq()) + sz(2 * (size_t)d.F, d.d) + sz(d.d, d.F)) * d.L + sz(d.V, d.d);
+}
 
 // Walks the workspace layout; with base == nullptr it only measures.
 static size_t carve(const Dims& d, char* base, Buffers* b) {
@@ -94,13 +104,15 @@ static size_t carve(const Dims& d, char* base, Buffers* b) {
     Buffers t;
     t.h = (float*)take(R * d.d * 4);
     t.xn = take(R * d.d * e);
-    t.qkv = (float*)take(R * d.nqkv() * 4);
     t.q = take(R * d.nq() * e);
     t.k = take(R * d.nkv() * e);
     t.v = take(R * d.nkv() * e);
+    t.vt = take((size_t)d.nkv() * d.vt_rows() * e);
     t.attn = take(R * d.nq() * e);
     t.act = take(R * d.F * e);
-    t.part = (float*)take((size_t)SSD_MAX_SPLIT * R * d.d * 4);
+    const size_t pc = d.nqkv() > d.d ? d.nqkv() : d.d;
+    t.part = (float*)take((size_t)SSD_MAX_SPLIT * R * pc * 4);
+    t.packed = take(packed_bytes(d));
     t.lm_part = (float*)take(R * (size_t)tiles * 3 * 4);
     t.row_max = (float*)take(R * 4);
     t.row_arg = (int*)take(R * 4);
@@ -109,7 +121,7 @@ static size_t carve(const Dims& d, char* base, Buffers* b) {
     t.row_pos = (int*)take(R * 4);
     t.row_node = (int*)take(R * 4);
     t.raw_tok = (int*)take(R * 4);
-    const size_t cache = (size_t)d.L * d.max_seqs * d.Hkv * d.max_seq_len * d.dh * e;
+    const size_t cache = (size_t)d.L * d.max_seqs * d.Hkv * d.seq_stride() * d.dh * e;
     t.kcache = take(cache);
     t.vcache = take(cache);
     t.rope_cos = (float*)take((size_t)d.max_seq_len * (d.dh / 2) * 4);
@@ -150,11 +162,27 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     if (!c) { g_create_err = "host allocation failed"; return SSD_ENOMEM; }
     c->dm = d;
     carve(d, (char*)workspace, &c->b);
-    c->lw.resize(d.L);
-    for (int l = 0; l < d.L; ++l)
-        c->lw[l] = LayerW{w->wqkv[l], w->wo[l], w->wgu[l], w->wdown[l], w->norm1[l], w->norm2[l]};
-    c->embed = w->embed; c->lm_head = w->lm_head; c->final_norm = w->final_norm;
     c->stream = (hipStream_t)hip_stream;
+    c->part_cols = d.nqkv() > d.d ? d.nqkv() : d.d;
+    // weights: keep the caller's pointers, and repack what tiles into MFMA fragment order
+    {
+        char* pk = (char*)c->b.packed;
+        auto mk = [&](const void* raw, int N, int K) {
+            Wt t{raw, nullptr, N, K};
+            if (packable(d, N, K)) {
+                t.packed = pk;
+                launch_pack_weights(raw, pk, N, K, c->stream);
+                pk += ((size_t)N * K * 2 + 255) & ~(size_t)255;
+            }
+            return t;
+        };
+        c->lw.resize(d.L);
+        for (int l = 0; l < d.L; ++l)
+            c->lw[l] = LayerW{mk(w->wqkv[l], d.nqkv(), d.d), mk(w->wo[l], d.d, d.nq()), mk(w->wgu[l], 2 * d.F, d.d),
+                              mk(w->wdown[l], d.d, d.F), w->norm1[l], w->norm2[l]};
+        c->lm_head = mk(w->lm_head, d.V, d.d);
+    }
+    c->embed = w->embed; c->final_norm = w->final_norm;
     c->kernel_path = 1;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
@@ -308,14 +336,17 @@ struct Upload {           // block state to push before the forward (stateless A
     SeqState st;
 };
 
-static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const void* W, void* out, int M, int N, int K,
-                 int* n_split) {
+// out = X * W^T.  EPI_F32 writes *n_split partial sums (the consumer adds them in order);
+// EPI_SWIGLU treats W as [gate; up] and writes silu(gate)*up; EPI_LMHEAD writes *n_split
+// per-tile (max, arg, sumexp) triples per row.
+static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void* out, int M, int* n_split) {
     ProfScope ps(c, cls);
     *n_split = 1;
-    if (c->kernel_path == 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, N, K, n_split, c->stream))
+    if (c->kernel_path == 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, n_split, c->stream))
         return;
+    const int N = epi == EPI_SWIGLU ? W.N / 2 : W.N;
     *n_split = epi == EPI_LMHEAD ? lm_tiles_plain(N) : 1;
-    launch_gemm_plain(c, epi, X, W, out, M, N, K, c->stream);
+    launch_gemm_plain(c, epi, X, W.raw, out, M, N, W.K, c->stream);
 }
 
 // Runs one forward over the groups in `hd` (decode groups first).  raw / n_raw:
@@ -347,6 +378,8 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     c->stage_used[slot] = true;
 
     const int M = hd.M, ML = hd.M_logits;
+    int max_blen = 0;
+    for (int i = 0; i < hd.n_nodes; ++i) max_blen = std::max(max_blen, hd.nodes[i].blen);
     {
         ProfScope ps(c, KC_ROWS);
         launch_build_rows(c, st, hd.n_nodes);
@@ -357,24 +390,24 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
         const LayerW& w = c->lw[l];
         { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
         n_part = 0;
-        gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.qkv, M, d.nqkv(), d.d, &ns);
-        { ProfScope ps(c, KC_ROPE); launch_rope(c, M, l, st); }
+        gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.part, M, &ns);
+        { ProfScope ps(c, KC_ROPE); launch_rope(c, M, l, ns, st); }
         if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
         {
             ProfScope ps(c, KC_ATTN);
-            if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, M, l, st)))
+            if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, hd.n_nodes, max_blen, l, st)))
                 launch_attn_plain(c, M, l, st);
         }
-        gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, d.d, d.nq(), &ns);
+        gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);
         { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm2, ns, st); }
-        gemm(c, KC_GEMM_GU, EPI_SWIGLU, c->b.xn, w.wgu, c->b.act, M, d.F, d.d, &ns);
-        gemm(c, KC_GEMM_DOWN, EPI_F32, c->b.act, w.wdown, c->b.part, M, d.d, d.F, &ns);
+        gemm(c, KC_GEMM_GU, EPI_SWIGLU, c->b.xn, w.wgu, c->b.act, M, &ns);
+        gemm(c, KC_GEMM_DOWN, EPI_F32, c->b.act, w.wdown, c->b.part, M, &ns);
         n_part = ns;
     }
     if (ML > 0) {
         { ProfScope ps(c, KC_NORM); launch_norm(c, ML, c->final_norm, n_part, st); }
         int tiles = 0;
-        gemm(c, KC_LMHEAD, EPI_LMHEAD, c->b.xn, c->lm_head, c->b.lm_part, ML, d.V, d.d, &tiles);
+        gemm(c, KC_LMHEAD, EPI_LMHEAD, c->b.xn, c->lm_head, c->b.lm_part, ML, &tiles);
         { ProfScope ps(c, KC_LMMERGE); launch_lm_merge(c, ML, tiles, st); }
         { ProfScope ps(c, KC_ACCEPT); launch_accept(c, hd.n_groups, out, st); }
     }
@@ -388,10 +421,13 @@ static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_no
     GroupDesc& g = hd.groups[hd.n_groups];
     g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
     g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.pad = 0;
+    int vrows = hd.n_nodes ? hd.nodes[hd.n_nodes - 1].vrow0 + ((hd.nodes[hd.n_nodes - 1].blen + 63) & ~63) : 0;
     for (int j = 0; j < n_nodes; ++j) {
         NodeDesc& nd = hd.nodes[hd.n_nodes++];
         nd.seq = seq; nd.row0 = hd.M + j * blen; nd.blen = blen; nd.S = S; nd.group = hd.n_groups; nd.j = j;
-        nd.write_kv = mode != GM_DECODE; nd.pad = 0;
+        nd.write_kv = mode != GM_DECODE;
+        nd.vrow0 = vrows;
+        vrows += (blen + 63) & ~63;
     }
     hd.n_groups++;
     hd.M += n_nodes * blen;

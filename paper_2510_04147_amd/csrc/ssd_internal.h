@@ -31,7 +31,8 @@ struct GroupDesc {
 struct NodeDesc {
     int seq, row0, blen, S;
     int group, j;   // j = index of the node inside its group = number of drafts written in
-    int write_kv, pad;
+    int write_kv;
+    int vrow0;      // 64-aligned start of the node's rows in the transposed own-value buffer
 };
 
 struct FwdHeader {
@@ -73,19 +74,25 @@ struct Dims {
     int nkv() const { return Hkv * dh; }
     int nqkv() const { return (Hq + 2 * Hkv) * dh; }
     size_t esz() const { return dtype == SSD_F32 ? 4 : 2; }
+    // positions allocated per cache slot: whole 64-position tiles, so tile loads stay in bounds
+    int seq_stride() const { return (max_seq_len + 63) & ~63; }
+    // rows of the transposed own-value buffer: every node starts on a 64-row boundary
+    int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * SSD_MAX_NODES; }
 };
 
 // Workspace carve-up (all device pointers into the caller's workspace).
 struct Buffers {
     float* h;            // [max_rows, d] residual stream, fp32
     void* xn;            // [max_rows, d] normed rows, T
-    float* qkv;          // [max_rows, nqkv] fp32 projections before rotary embedding
     void* q;             // [max_rows, nq] T, after rotary
     void* k;             // [max_rows, nkv] T, after rotary (the node's own keys)
     void* v;             // [max_rows, nkv] T
+    void* vt;            // [Hkv][dh][vt_rows] T: the same values, position-contiguous (MFMA operand order)
     void* attn;          // [max_rows, nq] T
     void* act;           // [max_rows, F] T
-    float* part;         // [SSD_MAX_SPLIT, max_rows, max(d, nqkv)] fp32 split-K partial sums
+    float* part;         // [SSD_MAX_SPLIT, max_rows, max(d, nqkv)] fp32 split-K partial sums of the
+                         // QKV, O and down projections (summed in order by the consumer)
+    void* packed;        // fragment-order copies of the weights (bf16 models)
     float* lm_part;      // [max_rows, n_vtiles, 3] (max, arg as float bits, sumexp)
     float* row_max;      // [max_rows]
     int* row_arg;        // [max_rows]
@@ -94,8 +101,8 @@ struct Buffers {
     int* row_pos;        // [max_rows]
     int* row_node;       // [max_rows]
     int* raw_tok;        // [max_rows]
-    void* kcache;        // [L][max_seqs][Hkv][max_seq_len][dh] T
-    void* vcache;
+    void* kcache;        // [L][max_seqs][Hkv][seq_stride][dh] T, keys after rotary embedding
+    void* vcache;        // [L][max_seqs][Hkv][dh][seq_stride] T, position-contiguous
     float* rope_cos;     // [max_seq_len, dh/2]
     float* rope_sin;
     FwdHeader* fwd;      // device copy of the descriptor
@@ -105,8 +112,16 @@ struct Buffers {
     int lm_tiles;        // vocab tiles of the LM-head reduction
 };
 
+// A linear weight: the caller's row-major [N, K] matrix and, for bf16 models
+// whose shape allows it, the library's copy in MFMA fragment order.
+struct Wt {
+    const void* raw;
+    const void* packed;
+    int N, K;
+};
+
 struct LayerW {
-    const void *wqkv, *wo, *wgu, *wdown;
+    Wt wqkv, wo, wgu, wdown;
     const float *norm1, *norm2;
 };
 
@@ -114,8 +129,10 @@ struct ssd_ctx {
     Dims dm;
     Buffers b;
     std::vector<LayerW> lw;
-    const void *embed, *lm_head;
+    const void* embed;
+    Wt lm_head;
     const float* final_norm;
+    int part_cols;             // columns of one split-K partial buffer = max(d, nqkv)
     hipStream_t stream;
     int kernel_path;
     int cached_len[SSD_MAX_SEQS];
@@ -142,7 +159,8 @@ struct ssd_ctx {
 void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes);
 void launch_embed(const ssd_ctx* c, int M, hipStream_t st);
 void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st);
-void launch_rope(const ssd_ctx* c, int M, int layer, hipStream_t st);
+void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t st);
+void launch_rope(const ssd_ctx* c, int M, int layer, int n_part, hipStream_t st);
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
 void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st);
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);
@@ -154,6 +172,7 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
                        hipStream_t st);
 
 // MFMA path (bf16 only).  Return false if the shape is not supported.
-bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const void* W, void* out, int M, int N, int K,
-                      int* n_split, hipStream_t st);
-bool launch_attn_mfma(const ssd_ctx* c, int M, int layer, hipStream_t st);
+bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, void* out, int M, int* n_split,
+                      hipStream_t st);
+int lm_tiles_mfma(int V);
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hipStream_t st);

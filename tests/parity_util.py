@@ -55,8 +55,6 @@ def compare_record(rec, gpu, maxlogit_tol, margin_tol, conf_tol, conf_rtol):
                 co, cg = float(rec["c"][j][p]), float(gpu["row_conf"][j, p])
                 assert abs(cg - co) <= conf_rtol * co, f"confidence {cg} vs {co} at node {j} pos {p}"
 
-    # (1) the acceptance kernel must be exactly the chain walk applied to the GPU's own rows
-    n_next_cap = len(rec["next_drafts"]) if rec["next_drafts"] else 0
     return stats, tok_exempt_rows, masks
 
 
@@ -96,3 +94,32 @@ def check_forward(rec, gpu, n_draft_next, maxlogit_tol, margin_tol, conf_tol, co
             f"decision differs from the oracle with no near-tie: {got_acc}/{got_nxt} vs {rec['accepted']}/{rec['next_drafts']}"
         stats["decision_exempt"] += 1
     return stats
+
+
+def teacher_forced(eng, cfg, w, prompt, gen_len, block, N, dtype, max_blocks=None, seq=0, verbose=True, **tol):
+    """Runs the oracle's SSD (recording every forward), then replays every
+    recorded forward through the HIP entry points from the oracle's state and
+    compares.  Returns (oracle tokens, oracle stats, totals)."""
+    trace = []
+    ref, st = decode.ssd(w, cfg, prompt, gen_len, block, N, dtype=dtype, trace=trace, max_blocks=max_blocks)
+    eng.reset(seq)
+    eng.prefill_kv(seq, prompt, 0)
+    out = eng.new_out(1)
+    totals = dict(rows=0, tok_exempt=0, decision_exempt=0, max_dlogit=0.0, forwards=0)
+    P = len(prompt)
+    for i, rec in enumerate(trace):
+        if verbose:
+            print(f"forward {i}: S={rec['S']} drafts={len(rec['drafts'])}", flush=True)
+        if eng.cached_len(seq) < rec["S"]:          # previous block finished: append its (oracle) tokens
+            lo = eng.cached_len(seq) - P
+            eng.prefill_kv(seq, ref[lo:rec["S"] - P], eng.cached_len(seq))
+        bl = len(rec["tok"])
+        eng.verify_tree([seq], [rec["tok"]], [bits(rec["masked"])], [rec["S"]], [rec["drafts"]], N, out,
+                        block_len=[bl])
+        g = {k: v[0] for k, v in out.host().items()}
+        s = check_forward(rec, g, N, **tol)
+        for k in ("rows", "tok_exempt", "decision_exempt"):
+            totals[k] += s[k]
+        totals["max_dlogit"] = max(totals["max_dlogit"], s["max_dlogit"])
+        totals["forwards"] += 1
+    return ref, st, totals

@@ -9,6 +9,7 @@ import torch
 
 from oracle import decode
 from paper_2510_04147_amd import synth
+import parity_util
 from parity_util import bits, check_forward
 
 pytestmark = pytest.mark.gpu
@@ -32,27 +33,7 @@ def setup():
 
 
 def teacher_forced(eng, cfg, w, prompt, gen_len, block, N, **tol):
-    trace = []
-    ref, st = decode.ssd(w, cfg, prompt, gen_len, block, N, trace=trace)
-    eng.reset(0)
-    eng.prefill_kv(0, prompt, 0)
-    out = eng.new_out(1)
-    totals = dict(rows=0, tok_exempt=0, decision_exempt=0, max_dlogit=0.0, forwards=0)
-    P = len(prompt)
-    for i, rec in enumerate(trace):
-        print(f"forward {i}: S={rec['S']} drafts={len(rec['drafts'])}", flush=True)
-        if eng.cached_len(0) < rec["S"]:          # previous block finished: append its (oracle) tokens
-            lo = eng.cached_len(0) - P
-            eng.prefill_kv(0, ref[lo:rec["S"] - P], eng.cached_len(0))
-        bl = len(rec["tok"])
-        eng.verify_tree([0], [rec["tok"]], [bits(rec["masked"])], [rec["S"]], [rec["drafts"]], N, out, block_len=[bl])
-        g = {k: v[0] for k, v in out.host().items()}
-        s = check_forward(rec, g, N, **tol)
-        for k in ("rows", "tok_exempt", "decision_exempt"):
-            totals[k] += s[k]
-        totals["max_dlogit"] = max(totals["max_dlogit"], s["max_dlogit"])
-        totals["forwards"] += 1
-    return ref, st, totals
+    return parity_util.teacher_forced(eng, cfg, w, prompt, gen_len, block, N, torch.float64, **tol)
 
 
 def test_teacher_forced_verify_matches_oracle(setup):

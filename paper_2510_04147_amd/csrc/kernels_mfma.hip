@@ -58,28 +58,46 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s
 }
 
 // ------------------------------------------------------------------------
-// GEMM.  Work-group = WN x WK waves.  Wave (wn, wk) owns R n-tiles of 32 rows
-// and, of every K chunk of WK*KW columns, the KW columns [wk*KW, (wk+1)*KW).
+// GEMM.  Work-group = WN x WK waves.  Wave (wn, wk) owns one n-tile of 32
+// weight rows and, of every K chunk of WK*32 columns, the 32 columns
+// [32wk, 32wk+32) (two k16 steps).
+//
+// Software pipeline, all statically indexed:
+//   weights      a ring of DW chunks in registers per wave: the fragment loads
+//                of chunk c+DW-1 are issued while chunk c is multiplied;
+//   activations  loads of chunk c+PX are issued into a register ring, chunk c+1
+//                is written to the other half of a two-stage LDS buffer while
+//                chunk c is multiplied, one barrier per chunk.
+// With the chunk count known at compile time (NCH > 0) the loop is straight-line
+// code, so the compiler's wait counts are exact; NCH = 0 is the same pipeline as
+// a loop unrolled by DW with loads past the end clamped (in bounds, unused).
+// Every work-group starts its K walk at a different chunk and wraps, which
+// spreads the grid's weight streams over the HBM channels; the order depends
+// on the n-tile only, so a row's summation order is the same in every forward.
+// DBG is for measurement builds only (bit 0: no MFMA, bit 1: no activation
+// loads, bit 2: no epilogue); the library instantiates DBG = 0.
 // ------------------------------------------------------------------------
-template <int WN, int WK, int R, int MT, int KW, int EPI>
-__global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restrict__ X, const uint4* __restrict__ Wp,
-                                                           void* __restrict__ outv, int M, int N, int K, int k_len,
-                                                           size_t split_stride, int up_tile_off, int mask_id,
-                                                           int n_tiles_out) {
-    constexpr int T = WN * WK * 64, KC = WK * KW, KSTEPS = KW / 16, ROWS = MT * 32, LDW = KC + 8;
+template <int WN, int WK, int MT, int EPI, int NCH, int DBG = 0>
+__global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, const uint4* Wp, void* outv, int M, int N,
+                                                           int K, int k_len, size_t split_stride, int up_tile_off,
+                                                           int mask_id, int n_tiles_out) {
+    constexpr int R = 1;
+    constexpr int T = WN * WK * 64, KW = 32, KC = WK * KW, KSTEPS = KW / 16, ROWS = MT * 32, LDW = KC + 8;
+    constexpr int DW = 4, PX = 3;
     constexpr int XSEG = ROWS * (KC / 8);               // 16-byte segments per X chunk
     constexpr int XPT = (XSEG + T - 1) / T;             // per thread
+    constexpr int SPARE = 2 * ROWS * LDW;               // LDS element offset of the per-thread spare slots
     extern __shared__ uint4 smem_u4[];
-    bf16_t* xs = (bf16_t*)smem_u4;                      // [2][ROWS][LDW]
+    bf16_t* xs = (bf16_t*)smem_u4;                      // [2][ROWS][LDW] + spare
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave % WN, wk = wave / WN;
     const int lm = lane & 31, lh = lane >> 5;
     const int m0 = blockIdx.y * ROWS;
-    const int kbeg = blockIdx.z * k_len, nchunks = k_len / KC;
+    const int kbeg = blockIdx.z * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
     const int KS = K >> 4, NT = N >> 5;
 
-    // n-tiles of this wave.  SwiGLU: even waves take a gate tile, odd waves the up tile of
-    // the same 32 channels (tile index + up_tile_off); R is 1 there.
+    // n-tile of this wave.  SwiGLU: even waves take a gate tile, odd waves the up tile of
+    // the same 32 channels (tile index + up_tile_off).
     int nt[R];
     bool nt_ok[R];
     if (EPI == EPI_SWIGLU) {
@@ -87,84 +105,132 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
         nt_ok[0] = ch < up_tile_off;
         nt[0] = (nt_ok[0] ? ch : up_tile_off - 1) + ((wn & 1) ? up_tile_off : 0);
     } else {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            nt[r] = (blockIdx.x * WN + wn) * R + r;
-            nt_ok[r] = nt[r] < NT;
-            if (!nt_ok[r]) nt[r] = NT - 1;
-        }
+        nt[0] = blockIdx.x * WN + wn;
+        nt_ok[0] = nt[0] < NT;
+        if (!nt_ok[0]) nt[0] = NT - 1;
     }
-    const uint4* wbase[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) wbase[r] = Wp + ((size_t)nt[r] * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
+    const uint4* wbase = Wp + ((size_t)nt[0] * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
 
     floatx16 acc[R][MT];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[r][mt][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[0][mt][i] = 0.f;
 
-    uint4 wcur[R][KSTEPS], wnxt[R][KSTEPS], xreg[XPT];
-
-    auto load_w = [&](uint4(&dst)[R][KSTEPS], int c) {
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) dst[r][ks] = wbase[r][((size_t)c * (KC / 16) + ks) * 64];
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.z * 3u) % (unsigned)nchunks);
+    auto chunk_at = [&](int c) {
+        c = c < nchunks - 1 ? c : nchunks - 1;
+        c += rot;
+        return c >= nchunks ? c - nchunks : c;
     };
-    auto load_x = [&](int c) {
+
+    // per-thread activation segments (the same for every chunk); segments past the tile or
+    // past row M load row 0 / write a spare slot or zeros, so nothing branches
+    const bf16_t* xsrc[XPT];
+    int xdst[XPT];
+    bool xok[XPT];
+#pragma unroll
+    for (int i = 0; i < XPT; ++i) {
+        const int seg = tid + i * T;
+        const int m = seg / (KC / 8), sg = seg - m * (KC / 8);
+        xok[i] = seg < XSEG && m0 + m < M;
+        xsrc[i] = X + (size_t)(xok[i] ? m0 + m : 0) * K + kbeg + sg * 8;
+        xdst[i] = seg < XSEG ? m * LDW + sg * 8 : SPARE + tid * 8;
+    }
+
+    // the rings are scalars-in-arrays with compile-time indices only
+    uint4 w0[KSTEPS], w1[KSTEPS], w2[KSTEPS], w3[KSTEPS];
+    uint4 x0[XPT], x1[XPT], x2[XPT];
+#define SSD_WSLOT(i) ((i) % DW == 0 ? w0 : (i) % DW == 1 ? w1 : (i) % DW == 2 ? w2 : w3)
+#define SSD_XSLOT(i) ((i) % PX == 0 ? x0 : (i) % PX == 1 ? x1 : x2)
+    auto issue_w = [&](uint4* dst, int c) {
+        const uint4* p = wbase + (size_t)chunk_at(c) * (KC / 16) * 64;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = p[ks * 64];
+    };
+    auto issue_x = [&](uint4* dst, int c) {
+        const size_t off = (size_t)chunk_at(c) * KC;
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int seg = tid + i * T;
-            const int m = seg / (KC / 8), s = seg - m * (KC / 8);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (seg < XSEG && m0 + m < M)
-                v = *(const uint4*)(X + (size_t)(m0 + m) * K + kbeg + c * KC + s * 8);
-            xreg[i] = v;
+            if (DBG & 2)
+                dst[i] = make_uint4(c, c, c, c);
+            else
+                dst[i] = *(const uint4*)(xsrc[i] + off);
         }
     };
-    auto store_x = [&](int buf) {
+    auto stage_x = [&](const uint4* src, int buf) {
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int seg = tid + i * T;
-            const int m = seg / (KC / 8), s = seg - m * (KC / 8);
-            if (seg < XSEG) *(uint4*)(xs + ((size_t)buf * ROWS + m) * LDW + s * 8) = xreg[i];
+            uint4 v = src[i];
+            if (!xok[i]) v = make_uint4(0, 0, 0, 0);
+            const int off = xdst[i] < SPARE ? buf * ROWS * LDW + xdst[i] : xdst[i];
+            *(uint4*)(xs + off) = v;
         }
     };
-
-    load_x(0);
-    load_w(wcur, 0);
-    store_x(0);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        const bool more = c + 1 < nchunks;
-        if (more) {
-            load_x(c + 1);
-            load_w(wnxt, c + 1);
-        }
-        const bf16_t* xb = xs + (size_t)(c & 1) * ROWS * LDW + wk * KW + lh * 8;
+    // all activation fragments of the chunk are read from LDS first, then the MFMAs run back
+    // to back: one exposed LDS latency per chunk instead of one per MFMA
+    auto multiply = [&](const uint4* w, int buf) {
+        const bf16_t* xb = xs + (size_t)buf * ROWS * LDW + wk * KW + lh * 8;
+        bf16x8 xf[KSTEPS][MT];
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xf[ks][mt] = *(const bf16x8*)(xb + (size_t)(mt * 32 + lm) * LDW + ks * 16);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
+            const uint4 wv = w[ks];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                const bf16x8 xf = *(const bf16x8*)(xb + (size_t)(mt * 32 + lm) * LDW + ks * 16);
+                if (DBG & 1)
+                    acc[0][mt][0] += __uint_as_float(wv.x ^ wv.w) + __uint_as_float(((const uint4*)&xf[ks][mt])->x);
+                else
+                    acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf[ks][mt], acc[0][mt], 0, 0, 0);
+            }
+        }
+    };
+
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const uint4 wv = wcur[r][ks];
-                    acc[r][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf, acc[r][mt], 0, 0, 0);
+    for (int u = 0; u < PX; ++u) issue_x(SSD_XSLOT(u), u);
+#pragma unroll
+    for (int u = 0; u < DW - 1; ++u) issue_w(SSD_WSLOT(u), u);
+    stage_x(x0, 0);
+    __syncthreads();
+    if constexpr (NCH > 0) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
+            if (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
+            multiply(SSD_WSLOT(c), c & 1);
+            if (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
+            __syncthreads();
+        }
+    } else {
+        constexpr int UN = DW * PX;                     // ring slots repeat with this period
+        for (int c0 = 0; c0 < nchunks; c0 += UN) {
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int c = c0 + u;
+                if (c < nchunks) {
+                    issue_x(SSD_XSLOT(u + PX), c + PX);
+                    issue_w(SSD_WSLOT(u + DW - 1), c + DW - 1);
+                    multiply(SSD_WSLOT(u), u & 1);
+                    stage_x(SSD_XSLOT(u + 1), (u + 1) & 1);
+                    __syncthreads();
                 }
             }
         }
-        if (more) {
-            store_x((c + 1) & 1);
+    }
+#undef SSD_WSLOT
+#undef SSD_XSLOT
+    if (DBG & 4) {
+        float sum = 0.f;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int ks = 0; ks < KSTEPS; ++ks) wcur[r][ks] = wnxt[r][ks];
-        }
-        __syncthreads();
+            for (int i = 0; i < 16; ++i) sum += acc[0][mt][i];
+        if (sum == 1.2345f) *(float*)outv = sum;
+        return;
     }
 
     // ---- reduce the WK k-slices of the work-group through LDS, in order wk = 1, 2, ...
@@ -175,11 +241,9 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
         if (!lead) {
             float* dst = red + ((size_t)((wk - 1) * WN + wn) * VALS) * 64 + lane;
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) dst[((r * MT + mt) * 16 + i) * 64] = acc[r][mt][i];
+                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[0][mt][i];
         }
         __syncthreads();
         if (lead) {
@@ -187,11 +251,9 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
             for (int w2 = 1; w2 < WK; ++w2) {
                 const float* src = red + ((size_t)((w2 - 1) * WN + wn) * VALS) * 64 + lane;
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) acc[r][mt][i] += src[((r * MT + mt) * 16 + i) * 64];
+                    for (int i = 0; i < 16; ++i) acc[0][mt][i] += src[(mt * 16 + i) * 64];
             }
         }
     }
@@ -199,18 +261,16 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
     // ---- epilogues.  Lane (lm, lh) holds, per tile, rows n = 8*(i/4) + 4*lh + i%4 of column m = lm.
     if (EPI == EPI_F32) {
         float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (!lead || !nt_ok[r]) continue;
+        if (lead && nt_ok[0]) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int m = m0 + mt * 32 + lm;
                 if (m >= M) continue;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = nt[r] * 32 + g * 8 + lh * 4;
+                    const int n = nt[0] * 32 + g * 8 + lh * 4;
                     *(float4*)(out + (size_t)m * N + n) =
-                        make_float4(acc[r][mt][g * 4], acc[r][mt][g * 4 + 1], acc[r][mt][g * 4 + 2], acc[r][mt][g * 4 + 3]);
+                        make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
                 }
             }
         }
@@ -248,7 +308,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
             }
         }
     } else if (lead) {
-        // LM head: per (row, wave) partial over the wave's R*32 vocabulary rows
+        // LM head: per (row, wave) partial over the wave's 32 vocabulary rows
         float* out = (float*)outv;
         const int tile_out = blockIdx.x * WN + wn;
 #pragma unroll
@@ -256,14 +316,10 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
             float bm = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!nt_ok[r]) continue;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int n = nt[r] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                    const float v = acc[r][mt][i];
-                    if (n != mask_id && v > bm) { bm = v; bi = n; }
-                }
+            for (int i = 0; i < 16; ++i) {
+                const int n = nt[0] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                const float v = acc[0][mt][i];
+                if (n != mask_id && v > bm) { bm = v; bi = n; }
             }
             {
                 const float om = __shfl_xor(bm, 32, 64);
@@ -272,13 +328,9 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
             }
             float se = 0.f;
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!nt_ok[r]) continue;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int n = nt[r] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                    if (n != mask_id) se += expf(acc[r][mt][i] - bm);
-                }
+            for (int i = 0; i < 16; ++i) {
+                const int n = nt[0] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                if (n != mask_id) se += expf(acc[0][mt][i] - bm);
             }
             se += __shfl_xor(se, 32, 64);
             const int m = m0 + mt * 32 + lm;
@@ -295,24 +347,20 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* __restr
 // ------------------------------------------------------------------------
 // launcher
 // ------------------------------------------------------------------------
-struct GemmPlan {
-    int split;     // work-groups along K (global split, partial sums)
-};
-
 static int env_int(const char* name, int dflt) {
     const char* s = getenv(name);
     return s ? atoi(s) : dflt;
 }
 
-template <int WN, int WK, int R, int MT, int KW, int EPI>
+template <int WN, int WK, int MT, int EPI, int NCH>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
                        int up_tile_off, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
-    constexpr int KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
-    constexpr size_t xbytes = (size_t)2 * ROWS * LDW * 2;
-    constexpr size_t rbytes = WK > 1 ? (size_t)(WK - 1) * WN * R * MT * 16 * 64 * 4 : 0;
+    constexpr int KC = WK * 32, ROWS = MT * 32, LDW = KC + 8;
+    constexpr size_t xbytes = (size_t)2 * ROWS * LDW * 2 + (size_t)WN * WK * 64 * 16;   // two stages + spare slots
+    constexpr size_t rbytes = WK > 1 ? (size_t)(WK - 1) * WN * MT * 16 * 64 * 4 : (size_t)(WN / 2) * MT * 16 * 64 * 4;
     constexpr size_t smem = xbytes > rbytes ? xbytes : rbytes;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = k_gemm_mfma<WN, WK, R, MT, KW, EPI>;
+    auto kern = k_gemm_mfma<WN, WK, MT, EPI, NCH>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -320,73 +368,97 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
         attr_done = true;
     }
     const int tiles = EPI == EPI_SWIGLU ? up_tile_off : N / 32;
-    const int per_wg = EPI == EPI_SWIGLU ? WN / 2 : WN * R;
+    const int per_wg = EPI == EPI_SWIGLU ? WN / 2 : WN;
     dim3 grid((tiles + per_wg - 1) / per_wg, m_chunks, split);
     hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K / split, split_stride,
                        up_tile_off, mask_id, n_tiles_out);
     return true;
 }
 
-template <int WN, int WK, int R, int KW, int EPI>
+// Row tiles per pass: 1 (a stepwise forward of one block), 2, or 5 (a 5-node tree);
+// other row counts round up (padding rows are zero and never stored).
+template <int WN, int WK, int EPI, int NCH>
 static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
                       size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
                       hipStream_t st) {
 #define SSD_MT_CASE(v)                                                                                          \
     case v:                                                                                                     \
-        return launch_one<WN, WK, R, v, KW, EPI>(X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id, \
-                                                 n_tiles_out, m_chunks, st);
+        return launch_one<WN, WK, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,  \
+                                               n_tiles_out, m_chunks, st);
     switch (mt) {
         SSD_MT_CASE(1)
         SSD_MT_CASE(2)
-        SSD_MT_CASE(3)
-        SSD_MT_CASE(4)
         SSD_MT_CASE(5)
     }
 #undef SSD_MT_CASE
     return false;
 }
 
+// Chunk counts with a straight-line kernel; anything else takes the looped one (NCH = 0).
+template <int WN, int WK, int EPI>
+static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
+                       size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
+                       hipStream_t st) {
+#define SSD_NCH_CASE(v)                                                                                           \
+    case v:                                                                                                       \
+        return launch_mt<WN, WK, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,      \
+                                         n_tiles_out, m_chunks, st);
+    if (EPI == EPI_F32) {
+        switch (nch) {
+            SSD_NCH_CASE(8)
+            SSD_NCH_CASE(16)
+            SSD_NCH_CASE(24)
+            SSD_NCH_CASE(32)
+            SSD_NCH_CASE(64)
+        }
+    } else {
+        switch (nch) { SSD_NCH_CASE(64) }
+    }
+#undef SSD_NCH_CASE
+    return launch_mt<WN, WK, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id, n_tiles_out,
+                                     m_chunks, st);
+}
+
 int lm_tiles_mfma(int V) { return V / 32; }
 
 // Split along K across work-groups: a function of the weight shape only.
-static int pick_split(int N, int K, int kc, int want) {
+static int pick_split(int K, int kc, int want) {
     int s = want;
     while (s > 1 && (K % (s * kc)) != 0) --s;
-    (void)N;
     return s < 1 ? 1 : s;
 }
 
+#ifndef SSD_KERNELS_ONLY
 bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, void* out, int M, int* n_split,
                       hipStream_t st) {
     if (!W.packed) return false;
     const int N = W.N, K = W.K;
-    constexpr int KW = 64, WN = 4, WK = 2, KC = WK * KW;
+    constexpr int WN = 4, WK = 2, KC = WK * 32;
     if (K % KC) return false;
     // rows per pass: up to 160; more rows re-stream the weights per 160-row chunk
-    const int mt = M >= 160 ? 5 : (M + 31) / 32;
+    const int mt = M <= 32 ? 1 : M <= 64 ? 2 : 5;
     const int rows = mt * 32, m_chunks = (M + rows - 1) / rows;
     const bf16_t* x = (const bf16_t*)X;
     const uint4* wp = (const uint4*)W.packed;
     const size_t stride = (size_t)c->dm.max_rows * (size_t)c->part_cols;
     if (epi == EPI_SWIGLU) {
-        // W = [2F, d]: gate rows then up rows; N is passed as F to the kernel's store
+        // W = [2F, d]: gate rows then up rows; the kernel's N is F
         const int F = N / 2;
         if (F % 32) return false;
         *n_split = 1;
-        return launch_mt<WN, WK, 1, KW, EPI_SWIGLU>(mt, x, wp, out, M, F, K, 1, 0, F / 32, -1, 0, m_chunks, st);
+        return launch_nch<WN, WK, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, F, K, 1, 0, F / 32, -1, 0, m_chunks, st);
     }
     if (epi == EPI_LMHEAD) {
         *n_split = lm_tiles_mfma(N);
-        return launch_mt<WN, WK, 1, KW, EPI_LMHEAD>(mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
+        return launch_nch<WN, WK, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
     }
-    int want = 1;
-    if (N <= 8192) want = env_int("SSD_SPLIT_SMALLN", 8);
-    else want = env_int("SSD_SPLIT_LARGEN", 2);
+    int want = N <= 8192 ? env_int("SSD_SPLIT_SMALLN", 8) : env_int("SSD_SPLIT_LARGEN", 2);
     if (want > SSD_MAX_SPLIT) want = SSD_MAX_SPLIT;
-    const int split = pick_split(N, K, KC, want);
+    const int split = pick_split(K, KC, want);
     *n_split = split;
-    return launch_mt<WN, WK, 1, KW, EPI_F32>(mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    return launch_nch<WN, WK, EPI_F32>(K / split / KC, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
 }
+#endif
 
 // ------------------------------------------------------------------------
 // a4: shared-prefix bidirectional attention on the matrix cores.
@@ -546,4 +618,47 @@ bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hi
         return false;
 #undef SSD_ATTN_ARGS
     return true;
+}
+
+// ------------------------------------------------------------------------
+// Measurement aid: a pure read of `bytes` with the access pattern of the
+// GEMM's weight stream (each wave walks its own contiguous region with
+// 16-byte loads, DEPTH independent loads in flight).  It gives the HBM read
+// rate the chip sustains for that pattern: the practical ceiling the GEMM is
+// measured against.
+// ------------------------------------------------------------------------
+template <int DEPTH>
+__global__ __launch_bounds__(512) void k_stream_read(const uint4* src, size_t n16_per_wave, unsigned* sink) {
+    const int lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const uint4* p = src + wave * n16_per_wave + lane;
+    unsigned acc = 0;
+    for (size_t i = 0; i < n16_per_wave; i += 64 * DEPTH) {
+        uint4 v[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) v[d] = p[i + (size_t)d * 64];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;      // practically never true; keeps the loads alive
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_debug_stream_read(const void* src, size_t bytes,
+                                                                            int work_groups, int waves_per_wg,
+                                                                            int depth, void* sink, void* stream) {
+    if (!src || !sink || work_groups < 1 || waves_per_wg < 1 || waves_per_wg > 8) return SSD_EINVAL;
+    const size_t waves = (size_t)work_groups * waves_per_wg;
+    size_t per = bytes / 16 / waves;
+    per -= per % (64 * 16);                      // whole unrolled steps for every depth
+    if (per == 0) return SSD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (depth == 16)
+        k_stream_read<16><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
+    else if (depth == 8)
+        k_stream_read<8><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
+    else if (depth == 4)
+        k_stream_read<4><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
+    else
+        return SSD_EINVAL;
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
 }

@@ -20,12 +20,24 @@
 //     a row's arithmetic never involves another row: a row is bit-identical in
 //     a 1-node and an (N+1)-node forward.
 #include <cstdlib>
+#include <type_traits>
 
 #include "ssd_internal.h"
 
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Compile-time loop: f(integral_constant<int, C>) for C in [BEGIN, END).  The ring slots of the
+// GEMM pipeline are selected by these constants, so no register array is ever indexed by a
+// run-time value (which would push it to scratch memory).
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (BEGIN < END) {
+        f(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(f);
+    }
+}
 
 __device__ __forceinline__ uint16_t f2bf_m(float f) {
     uint32_t x = __float_as_uint(f);
@@ -190,26 +202,24 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         }
     };
 
-#pragma unroll
-    for (int u = 0; u < PX; ++u) issue_x(SSD_XSLOT(u), u);
-#pragma unroll
-    for (int u = 0; u < DW - 1; ++u) issue_w(SSD_WSLOT(u), u);
+    static_for<0, PX>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_x(SSD_XSLOT(u), u); });
+    static_for<0, DW - 1>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_w(SSD_WSLOT(u), u); });
     stage_x(x0, 0);
     __syncthreads();
     if constexpr (NCH > 0) {
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            if (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
-            if (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
+        static_for<0, NCH>([&](auto ic) {
+            constexpr int c = decltype(ic)::value;
+            if constexpr (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
+            if constexpr (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
             multiply(SSD_WSLOT(c), c & 1);
-            if (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
+            if constexpr (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
             __syncthreads();
-        }
+        });
     } else {
         constexpr int UN = DW * PX;                     // ring slots repeat with this period
         for (int c0 = 0; c0 < nchunks; c0 += UN) {
-#pragma unroll
-            for (int u = 0; u < UN; ++u) {
+            static_for<0, UN>([&](auto ic) {
+                constexpr int u = decltype(ic)::value;
                 const int c = c0 + u;
                 if (c < nchunks) {
                     issue_x(SSD_XSLOT(u + PX), c + PX);
@@ -218,7 +228,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
                     stage_x(SSD_XSLOT(u + 1), (u + 1) & 1);
                     __syncthreads();
                 }
-            }
+            });
         }
     }
 #undef SSD_WSLOT

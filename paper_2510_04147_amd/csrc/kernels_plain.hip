@@ -85,19 +85,36 @@ __global__ void k_embed(const T* __restrict__ embed, const int* __restrict__ row
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)row * d + i] = ld_f(e + i);
 }
 
-// a2/a6/a9: h += sum of split-K partial sums (fixed order), then RMSNorm.
-template <typename T>
-__global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float* __restrict__ part, int n_part,
-                                              size_t part_stride, const float* __restrict__ gain,
-                                              T* __restrict__ xn, int d, float eps) {
-    const int row = blockIdx.x;
-    float* hr = h + (size_t)row * d;
+// a2/a6/a9: h += sum of split-K partial sums (fixed order s = 0, 1, ...), then RMSNorm.
+// One work-group per row; every thread owns up to NORM_J float4 groups of the row, all
+// partial-sum loads are issued before the first add.
+#define NORM_J 8   // 256 threads x 8 float4 = rows up to 8192 wide
+__device__ __forceinline__ void st4(float* p, float a, float b, float c, float d) { *(float4*)p = make_float4(a, b, c, d); }
+__device__ __forceinline__ void st4(bf16_t* p, float a, float b, float c, float d) {
+    *(uint2*)p = make_uint2((uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16), (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16));
+}
+
+template <typename T, int NP>
+__device__ __forceinline__ void norm_row(float* hr, const float* pr, size_t part_stride, const float* gain, T* xr,
+                                         int d, float eps) {
+    const int n4 = d >> 2;
+    float4 v[NORM_J];
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = hr[i];
-        for (int s = 0; s < n_part; ++s) v += part[s * part_stride + (size_t)row * d + i];
-        if (n_part) hr[i] = v;
-        ss += v * v;
+#pragma unroll
+    for (int j = 0; j < NORM_J; ++j) {
+        const int i4 = threadIdx.x + j * 256;
+        if (i4 < n4) {
+            v[j] = ((const float4*)hr)[i4];
+            float4 pv[NP > 0 ? NP : 1];
+#pragma unroll
+            for (int s = 0; s < NP; ++s) pv[s] = ((const float4*)(pr + s * part_stride))[i4];
+#pragma unroll
+            for (int s = 0; s < NP; ++s) {
+                v[j].x += pv[s].x; v[j].y += pv[s].y; v[j].z += pv[s].z; v[j].w += pv[s].w;
+            }
+            if (NP > 0) ((float4*)hr)[i4] = v[j];
+            ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+        }
     }
     __shared__ float red[4];
     ss = wave_sum(ss);
@@ -105,58 +122,128 @@ __global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float
     __syncthreads();
     const float tot = (red[0] + red[1]) + (red[2] + red[3]);
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) st_f(xn + (size_t)row * d + i, hr[i] * r * gain[i]);
-}
-
-// Rotary embedding (rotate-half pairing) of Q and K from the fp32 projections,
-// conversion to the operand type, and the cache write for nodes that own
-// finished tokens.
-template <typename T>
-__global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ part,
-                                              int n_part, size_t part_stride, const int* __restrict__ row_pos, const int* __restrict__ row_node,
-                                              const float* __restrict__ cosT, const float* __restrict__ sinT,
-                                              T* __restrict__ q, T* __restrict__ k, T* __restrict__ v,
-                                              T* __restrict__ vt, int vt_rows,
-                                              T* __restrict__ kcache, T* __restrict__ vcache, int Hq, int Hkv,
-                                              int dh, int layer, int max_seqs, int seq_stride) {
-    const int row = blockIdx.x;
-    const int pos = row_pos[row];
-    const NodeDesc nd = fw->nodes[row_node[row]];
-    const int half = dh >> 1;
-    const int nq = Hq * dh, nkv = Hkv * dh, nqkv = nq + 2 * nkv;
-    const float* src = part + (size_t)row * nqkv;
-    // sum of the projection's split-K partial sums, in split order
-    auto val = [&](int col) {
-        float v = src[col];
-        for (int s = 1; s < n_part; ++s) v += src[s * part_stride + col];
-        return v;
-    };
-    const size_t cbase = (((size_t)layer * max_seqs + nd.seq) * Hkv) * (size_t)seq_stride * dh;
-    const int vrow = nd.vrow0 + (row - nd.row0);
-    for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += 256) {
-        const int head = idx / half, i = idx - head * half;
-        const float x1 = val(head * dh + i), x2 = val(head * dh + i + half);
-        const float c = cosT[(size_t)pos * half + i], s = sinT[(size_t)pos * half + i];
-        const float o1 = x1 * c - x2 * s, o2 = x2 * c + x1 * s;
-        if (head < Hq) {
-            st_f(q + (size_t)row * nq + head * dh + i, o1);
-            st_f(q + (size_t)row * nq + head * dh + i + half, o2);
-        } else {
-            const int kh = head - Hq;
-            st_f(k + (size_t)row * nkv + kh * dh + i, o1);
-            st_f(k + (size_t)row * nkv + kh * dh + i + half, o2);
-            if (nd.write_kv) {
-                T* dst = kcache + cbase + ((size_t)kh * seq_stride + pos) * dh;
-                st_f(dst + i, o1);
-                st_f(dst + i + half, o2);
-            }
+#pragma unroll
+    for (int j = 0; j < NORM_J; ++j) {
+        const int i4 = threadIdx.x + j * 256;
+        if (i4 < n4) {
+            const float4 g = ((const float4*)gain)[i4];
+            st4(xr + 4 * i4, v[j].x * r * g.x, v[j].y * r * g.y, v[j].z * r * g.z, v[j].w * r * g.w);
         }
     }
-    for (int idx = threadIdx.x; idx < nkv; idx += 256) {
-        const float x = val(nq + nkv + idx);
-        st_f(v + (size_t)row * nkv + idx, x);
-        st_f(vt + (size_t)idx * vt_rows + vrow, x);
-        if (nd.write_kv) st_f(vcache + cbase + (size_t)idx * seq_stride + pos, x);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float* __restrict__ part, int n_part,
+                                              size_t part_stride, const float* __restrict__ gain,
+                                              T* __restrict__ xn, int d, float eps) {
+    const int row = blockIdx.x;
+    float* hr = h + (size_t)row * d;
+    const float* pr = part + (size_t)row * d;
+    T* xr = xn + (size_t)row * d;
+    switch (n_part) {
+        case 0: norm_row<T, 0>(hr, pr, part_stride, gain, xr, d, eps); break;
+        case 1: norm_row<T, 1>(hr, pr, part_stride, gain, xr, d, eps); break;
+        case 2: norm_row<T, 2>(hr, pr, part_stride, gain, xr, d, eps); break;
+        case 4: norm_row<T, 4>(hr, pr, part_stride, gain, xr, d, eps); break;
+        case 8: norm_row<T, 8>(hr, pr, part_stride, gain, xr, d, eps); break;
+        default: {
+            // any other split count: fold the partial sums into h first, in order
+            for (int i = threadIdx.x; i < d; i += 256) {
+                float v = hr[i];
+                for (int s = 0; s < n_part; ++s) v += pr[s * part_stride + i];
+                hr[i] = v;
+            }
+            __syncthreads();
+            norm_row<T, 0>(hr, pr, part_stride, gain, xr, d, eps);
+        }
+    }
+}
+
+// Rotary embedding (rotate-half pairing) of Q and K from the fp32 projection (the sum of its
+// split-K partial sums, in split order), conversion to the operand type, the transposed
+// (position-contiguous) copy of V, and the cache write for nodes that own finished tokens.
+// One work-group per (node, 32-row tile, head of Q, K or V): 32 rows x 8 column groups.
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ part,
+                                              int n_part, size_t part_stride, const float* __restrict__ cosT,
+                                              const float* __restrict__ sinT, T* __restrict__ q, T* __restrict__ k,
+                                              T* __restrict__ v, T* __restrict__ vt, int vt_rows,
+                                              T* __restrict__ kcache, T* __restrict__ vcache, int Hq, int Hkv,
+                                              int layer, int max_seqs, int seq_stride) {
+    constexpr int HALF = DH / 2, PT = HALF / 8;          // q/k: values of each rotary half per thread
+    constexpr int VPT = DH / 8;                          // v: values per thread
+    const NodeDesc nd = fw->nodes[blockIdx.x];
+    const int r0 = blockIdx.y * 32;
+    if (r0 >= nd.blen) return;
+    const int hh = blockIdx.z, tid = threadIdx.x, r = tid >> 3, cg = tid & 7;
+    const bool rvalid = r0 + r < nd.blen;
+    const int row = nd.row0 + (rvalid ? r0 + r : 0);
+    const int pos = nd.S + (rvalid ? r0 + r : 0);
+    const int nq = Hq * DH, nkv = Hkv * DH, nqkv = nq + 2 * nkv;
+    const float* src = part + (size_t)row * nqkv;
+    const size_t cbase = (((size_t)layer * max_seqs + nd.seq) * Hkv) * (size_t)seq_stride * DH;
+    auto load = [&](int col, float* dst, int n) {       // n values (multiple of 4) from column col
+#pragma unroll
+        for (int j = 0; j < n; j += 4) {
+            float4 a = *(const float4*)(src + col + j);
+            for (int sp = 1; sp < n_part; ++sp) {
+                const float4 b = *(const float4*)(src + sp * part_stride + col + j);
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            dst[j] = a.x; dst[j + 1] = a.y; dst[j + 2] = a.z; dst[j + 3] = a.w;
+        }
+    };
+    if (hh < Hq + Hkv) {
+        const int i0 = cg * PT;
+        float x1[PT], x2[PT], o1[PT], o2[PT];
+        load(hh * DH + i0, x1, PT);
+        load(hh * DH + i0 + HALF, x2, PT);
+#pragma unroll
+        for (int j = 0; j < PT; ++j) {
+            const float c = cosT[(size_t)pos * HALF + i0 + j], sn = sinT[(size_t)pos * HALF + i0 + j];
+            o1[j] = x1[j] * c - x2[j] * sn;
+            o2[j] = x2[j] * c + x1[j] * sn;
+        }
+        if (rvalid) {
+            T* dst = hh < Hq ? q + (size_t)row * nq + hh * DH : k + (size_t)row * nkv + (hh - Hq) * DH;
+#pragma unroll
+            for (int j = 0; j < PT; j += 4) {
+                st4(dst + i0 + j, o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
+                st4(dst + i0 + HALF + j, o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+            }
+            if (hh >= Hq && nd.write_kv) {
+                T* kc = kcache + cbase + ((size_t)(hh - Hq) * seq_stride + pos) * DH;
+#pragma unroll
+                for (int j = 0; j < PT; j += 4) {
+                    st4(kc + i0 + j, o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
+                    st4(kc + i0 + HALF + j, o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+                }
+            }
+        }
+    } else {
+        const int vh = hh - Hq - Hkv, c0 = cg * VPT;
+        __shared__ float tile[32][DH + 1];
+        float x[VPT];
+        load(nq + nkv + vh * DH + c0, x, VPT);
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) tile[r][c0 + j] = rvalid ? x[j] : 0.f;
+        if (rvalid) {
+            T* dst = v + (size_t)row * nkv + vh * DH + c0;
+#pragma unroll
+            for (int j = 0; j < VPT; j += 4) st4(dst + j, x[j], x[j + 1], x[j + 2], x[j + 3]);
+        }
+        __syncthreads();
+        // transposed copy: thread -> (column, group of rows); a node's rows start 64-aligned
+        constexpr int TPC = 256 / DH, RPT = 32 / TPC;    // threads per column, rows per thread
+        const int col = tid / TPC, rg = (tid % TPC) * RPT;
+        T* vd = vt + (size_t)(vh * DH + col) * vt_rows + nd.vrow0 + r0 + rg;
+#pragma unroll
+        for (int j = 0; j < RPT; j += 4) st4(vd + j, tile[rg + j][col], tile[rg + j + 1][col], tile[rg + j + 2][col], tile[rg + j + 3][col]);
+        if (nd.write_kv) {
+            T* vc = vcache + cbase + (size_t)(vh * DH + col) * seq_stride + nd.S + r0 + rg;
+            for (int j = 0; j < RPT; ++j)
+                if (r0 + rg + j < nd.blen) st_f(vc + j, tile[rg + j][col]);
+        }
     }
 }
 
@@ -495,21 +582,21 @@ void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStre
                                           c->dm.eps);
 }
 
-void launch_rope(const ssd_ctx* c, int M, int layer, int n_part, hipStream_t st) {
+void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st) {
     const Dims& d = c->dm;
     const size_t ps = (size_t)d.max_rows * c->part_cols;
-    if (d.dtype == SSD_F32)
-        k_rope<float><<<M, 256, 0, st>>>(c->b.fwd, c->b.part, n_part, ps, c->b.row_pos, c->b.row_node, c->b.rope_cos,
-                                         c->b.rope_sin, (float*)c->b.q, (float*)c->b.k, (float*)c->b.v,
-                                         (float*)c->b.vt, d.vt_rows(),
-                                         (float*)c->b.kcache, (float*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
-                                         d.max_seqs, d.seq_stride());
-    else
-        k_rope<bf16_t><<<M, 256, 0, st>>>(c->b.fwd, c->b.part, n_part, ps, c->b.row_pos, c->b.row_node, c->b.rope_cos,
-                                          c->b.rope_sin, (bf16_t*)c->b.q, (bf16_t*)c->b.k, (bf16_t*)c->b.v,
-                                          (bf16_t*)c->b.vt, d.vt_rows(),
-                                          (bf16_t*)c->b.kcache, (bf16_t*)c->b.vcache, d.Hq, d.Hkv, d.dh, layer,
-                                          d.max_seqs, d.seq_stride());
+    dim3 grid(n_nodes, (max_blen + 31) / 32, d.Hq + 2 * d.Hkv);
+#define SSD_ROPE_ARGS(T)                                                                                           \
+    c->b.fwd, c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin, (T*)c->b.q, (T*)c->b.k, (T*)c->b.v, (T*)c->b.vt, \
+        d.vt_rows(), (T*)c->b.kcache, (T*)c->b.vcache, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride()
+    if (d.dtype == SSD_F32) {
+        if (d.dh == 128) k_rope<float, 128><<<grid, 256, 0, st>>>(SSD_ROPE_ARGS(float));
+        else k_rope<float, 64><<<grid, 256, 0, st>>>(SSD_ROPE_ARGS(float));
+    } else {
+        if (d.dh == 128) k_rope<bf16_t, 128><<<grid, 256, 0, st>>>(SSD_ROPE_ARGS(bf16_t));
+        else k_rope<bf16_t, 64><<<grid, 256, 0, st>>>(SSD_ROPE_ARGS(bf16_t));
+    }
+#undef SSD_ROPE_ARGS
 }
 
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st) {

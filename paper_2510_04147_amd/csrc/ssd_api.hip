@@ -391,7 +391,7 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
         { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
         n_part = 0;
         gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.part, M, &ns);
-        { ProfScope ps(c, KC_ROPE); launch_rope(c, M, l, ns, st); }
+        { ProfScope ps(c, KC_ROPE); launch_rope(c, hd.n_nodes, max_blen, l, ns, st); }
         if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
         {
             ProfScope ps(c, KC_ATTN);

@@ -160,7 +160,7 @@ void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes);
 void launch_embed(const ssd_ctx* c, int M, hipStream_t st);
 void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st);
 void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t st);
-void launch_rope(const ssd_ctx* c, int M, int layer, int n_part, hipStream_t st);
+void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st);
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
 void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st);
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);

@@ -489,19 +489,25 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
 // ------------------------------------------------------------------------
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
+#define ATTN_WAVES 4   // waves per (node, head, query tile): wave w takes key tiles w, w+4, ...
+
 template <int DH>
-__global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__ fw, const bf16_t* __restrict__ q,
-                                                   const bf16_t* __restrict__ kown, const bf16_t* __restrict__ vt,
-                                                   const bf16_t* __restrict__ kcache, const bf16_t* __restrict__ vcache,
-                                                   bf16_t* __restrict__ out, int Hq, int Hkv, int layer, int max_seqs,
-                                                   int seq_stride, int vt_rows, float scale) {
+__global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* __restrict__ fw,
+                                                               const bf16_t* __restrict__ q,
+                                                               const bf16_t* __restrict__ kown,
+                                                               const bf16_t* __restrict__ vt,
+                                                               const bf16_t* __restrict__ kcache,
+                                                               const bf16_t* __restrict__ vcache,
+                                                               bf16_t* __restrict__ out, int Hq, int Hkv, int layer,
+                                                               int max_seqs, int seq_stride, int vt_rows, float scale) {
     constexpr int KST = DH / 16, DT = DH / 32;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    __shared__ float mrg[ATTN_WAVES - 1][DT * 16 + 2][64];          // partial (O^T, max, sum) of waves 1..3
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lm = lane & 31, lh = lane >> 5;
     const NodeDesc nd = fw->nodes[blockIdx.x];
     const int head = blockIdx.y, kvh = head / (Hq / Hkv);
-    const int qt = blockIdx.z * waves + wave;
-    if (qt * 32 >= nd.blen) return;
+    const int qt = blockIdx.z;
+    if (qt * 32 >= nd.blen) return;                                  // uniform over the work-group
     const int nq = Hq * DH, nkv = Hkv * DH;
     const int qrow_in = qt * 32 + lm;
     const bool qvalid = qrow_in < nd.blen;
@@ -512,10 +518,10 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
     for (int ks = 0; ks < KST; ++ks) qf[ks] = *(const bf16x8*)(q + (size_t)qrow * nq + head * DH + ks * 16 + lh * 8);
 
     const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)seq_stride * DH;
-    const bf16_t* kc = kcache + cbase;                      // [pos][DH]
-    const bf16_t* vc = vcache + cbase;                      // [DH][seq_stride]
-    const bf16_t* ko = kown + (size_t)nd.row0 * nkv + kvh * DH;   // [row][nkv]
-    const bf16_t* vo = vt + (size_t)kvh * DH * vt_rows + nd.vrow0;   // [DH][vt_rows]
+    const bf16_t* kc = kcache + cbase;                              // [pos][DH]
+    const bf16_t* vc = vcache + cbase;                              // [DH][seq_stride]
+    const bf16_t* ko = kown + (size_t)nd.row0 * nkv + kvh * DH;     // [row][nkv]
+    const bf16_t* vo = vt + (size_t)kvh * DH * vt_rows + nd.vrow0;  // [DH][vt_rows]
 
     floatx16 oacc[DT];
 #pragma unroll
@@ -524,22 +530,22 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
     float m_run = -INFINITY, l_part = 0.f;
 
-    const int pre_tiles = (nd.S + 31) >> 5, own_tiles = (nd.blen + 31) >> 5;
-    for (int t = 0; t < pre_tiles + own_tiles; ++t) {
+    const int pre_tiles = (nd.S + 31) >> 5, n_tiles = pre_tiles + ((nd.blen + 31) >> 5);
+    // key fragment loads of one tile (rows past the end are clamped to row 0 and masked later)
+    auto load_k = [&](bf16x8(&kf)[KST], int t) {
         const bool own = t >= pre_tiles;
-        const int t0 = (own ? t - pre_tiles : t) * 32;     // first key of the tile, in its own index space
-        const int n_valid = (own ? nd.blen : nd.S) - t0;   // keys of this tile that exist (may exceed 32)
-        // ---- S^T = K Q^T
+        const int t0 = (own ? t - pre_tiles : t) * 32;
         const int krow = t0 + lm < (own ? nd.blen : nd.S) ? t0 + lm : 0;
         const bf16_t* kp = own ? ko + (size_t)krow * nkv : kc + (size_t)krow * DH;
-        floatx16 sacc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks) {
-            const bf16x8 kf = *(const bf16x8*)(kp + ks * 16 + lh * 8);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
-        }
+        for (int ks = 0; ks < KST; ++ks) kf[ks] = *(const bf16x8*)(kp + ks * 16 + lh * 8);
+    };
+    bf16x8 kf[KST], kn[KST];
+    if (wave < n_tiles) load_k(kf, wave);
+    for (int t = wave; t < n_tiles; t += ATTN_WAVES) {
+        const bool own = t >= pre_tiles;
+        const int t0 = (own ? t - pre_tiles : t) * 32;              // first key of the tile, in its own index space
+        const int n_valid = (own ? nd.blen : nd.S) - t0;            // keys of this tile that exist (may exceed 32)
         // ---- values of this tile, position-contiguous: two 4-position runs per step
         const bf16_t* vp = own ? vo : vc;
         const size_t vstride = own ? (size_t)vt_rows : (size_t)seq_stride;
@@ -552,6 +558,14 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
                 const bf16x4 lo = *(const bf16x4*)a, hi = *(const bf16x4*)(a + 8);
                 vf[dt][st] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
+        // ---- keys of this wave's next tile, in flight while this tile is processed
+        if (t + ATTN_WAVES < n_tiles) load_k(kn, t + ATTN_WAVES);
+        // ---- S^T = K Q^T
+        floatx16 sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
         // ---- online softmax over this lane's 16 keys (key = t0 + 8*(i/4) + 4*lh + i%4)
         float mx = -INFINITY;
 #pragma unroll
@@ -568,13 +582,13 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
         bf16x8 pf[2];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float p = expf(sacc[i] - m_new);          // 0 for masked keys
+            const float p = expf(sacc[i] - m_new);                  // 0 for masked keys
             psum += p;
             pf[i >> 3][i & 7] = (__bf16)p;
         }
         l_part = l_part * corr + psum;
         if (n_valid < 32) {
-            // keys past the end hold stale memory: zero them so 0 * garbage cannot produce NaN
+            // positions past the end hold stale memory: zero them so 0 * garbage cannot produce NaN
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -593,6 +607,32 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
             for (int st = 0; st < 2; ++st)
                 oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][st], pf[st], oacc[dt], 0, 0, 0);
         }
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks) kf[ks] = kn[ks];
+    }
+    // ---- merge the waves' partial results in wave order (fixed, independent of the forward's shape)
+    if (wave > 0) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mrg[wave - 1][dt * 16 + i][lane] = oacc[dt][i];
+        mrg[wave - 1][DT * 16][lane] = m_run;
+        mrg[wave - 1][DT * 16 + 1][lane] = l_part;
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 1; w < ATTN_WAVES; ++w) {
+        const float m2 = mrg[w - 1][DT * 16][lane], l2 = mrg[w - 1][DT * 16 + 1][lane];
+        if (m2 == -INFINITY) continue;                               // that wave had no tile
+        const float m_new = fmaxf(m_run, m2);
+        const float c1 = expf(m_run - m_new), c2 = expf(m2 - m_new);
+        l_part = l_part * c1 + l2 * c2;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[dt][i] = oacc[dt][i] * c1 + mrg[w - 1][dt * 16 + i][lane] * c2;
+        m_run = m_new;
     }
     const float l = l_part + __shfl_xor(l_part, 32, 64);
     const float inv = 1.0f / l;
@@ -613,17 +653,15 @@ __global__ __launch_bounds__(512) void k_attn_mfma(const FwdHeader* __restrict__
 
 bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hipStream_t st) {
     const Dims& d = c->dm;
-    const int qtiles = (max_blen + 31) / 32;
-    const int waves = qtiles < 8 ? qtiles : 8;
-    dim3 grid(n_nodes, d.Hq, (qtiles + waves - 1) / waves);
+    dim3 grid(n_nodes, d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
 #define SSD_ATTN_ARGS                                                                                                  \
     c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.k, (const bf16_t*)c->b.vt, (const bf16_t*)c->b.kcache,      \
         (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale
     if (d.dh == 128)
-        k_attn_mfma<128><<<grid, waves * 64, 0, st>>>(SSD_ATTN_ARGS);
+        k_attn_mfma<128><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
     else if (d.dh == 64)
-        k_attn_mfma<64><<<grid, waves * 64, 0, st>>>(SSD_ATTN_ARGS);
+        k_attn_mfma<64><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
     else
         return false;
 #undef SSD_ATTN_ARGS

@@ -87,20 +87,22 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s
 // spreads the grid's weight streams over the HBM channels; the order depends
 // on the n-tile only, so a row's summation order is the same in every forward.
 // DBG is for measurement builds only (bit 0: no MFMA, bit 1: no activation
-// loads, bit 2: no epilogue); the library instantiates DBG = 0.
+// loads, bit 2: no epilogue, bit 3: every chunk reads chunk 0's activations); the library
+// instantiates DBG = 0.
 // ------------------------------------------------------------------------
-template <int WN, int WK, int MT, int EPI, int NCH, int DBG = 0>
+template <int WN, int WK, int R, int MT, int EPI, int NCH, int DBG = 0, int DW = 4, int PX = 4, int KSTEPS = 2>
 __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, const uint4* Wp, void* outv, int M, int N,
                                                            int K, int k_len, size_t split_stride, int up_tile_off,
                                                            int mask_id, int n_tiles_out) {
-    constexpr int R = 1;
-    constexpr int T = WN * WK * 64, KW = 32, KC = WK * KW, KSTEPS = KW / 16, ROWS = MT * 32, LDW = KC + 8;
-    constexpr int DW = 4, PX = 3;
+    constexpr int T = WN * WK * 64, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
+    constexpr int NST = 3;                              // LDS stages
+    static_assert(DW >= 2 && DW <= 6 && PX >= 3 && PX <= 4, "ring depths");
+    static_assert(EPI != EPI_SWIGLU || R == 2 || WN % 2 == 0, "SwiGLU pairs gate and up tiles");
     constexpr int XSEG = ROWS * (KC / 8);               // 16-byte segments per X chunk
     constexpr int XPT = (XSEG + T - 1) / T;             // per thread
-    constexpr int SPARE = 2 * ROWS * LDW;               // LDS element offset of the per-thread spare slots
+    constexpr int SPARE = NST * ROWS * LDW;             // LDS element offset of the per-thread spare slots
     extern __shared__ uint4 smem_u4[];
-    bf16_t* xs = (bf16_t*)smem_u4;                      // [2][ROWS][LDW] + spare
+    bf16_t* xs = (bf16_t*)smem_u4;                      // [NST][ROWS][LDW] + spare
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave % WN, wk = wave / WN;
     const int lm = lane & 31, lh = lane >> 5;
@@ -108,26 +110,38 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
     const int kbeg = blockIdx.z * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
     const int KS = K >> 4, NT = N >> 5;
 
-    // n-tile of this wave.  SwiGLU: even waves take a gate tile, odd waves the up tile of
-    // the same 32 channels (tile index + up_tile_off).
+    // n-tiles of this wave.  SwiGLU pairs the gate tile of 32 channels with their up tile
+    // (tile index + up_tile_off): in one wave when R == 2, in an even/odd wave pair when R == 1.
     int nt[R];
     bool nt_ok[R];
     if (EPI == EPI_SWIGLU) {
-        const int ch = blockIdx.x * (WN / 2) + (wn >> 1);
-        nt_ok[0] = ch < up_tile_off;
-        nt[0] = (nt_ok[0] ? ch : up_tile_off - 1) + ((wn & 1) ? up_tile_off : 0);
+        const int ch = R == 2 ? blockIdx.x * WN + wn : blockIdx.x * (WN / 2) + (wn >> 1);
+        const bool ok = ch < up_tile_off;
+        const int chc = ok ? ch : up_tile_off - 1;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            nt_ok[r] = ok;
+            nt[r] = chc + ((R == 2 ? r == 1 : (wn & 1)) ? up_tile_off : 0);
+        }
     } else {
-        nt[0] = blockIdx.x * WN + wn;
-        nt_ok[0] = nt[0] < NT;
-        if (!nt_ok[0]) nt[0] = NT - 1;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            nt[r] = (blockIdx.x * WN + wn) * R + r;
+            nt_ok[r] = nt[r] < NT;
+            if (!nt_ok[r]) nt[r] = NT - 1;
+        }
     }
-    const uint4* wbase = Wp + ((size_t)nt[0] * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
+    const uint4* wbase[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) wbase[r] = Wp + ((size_t)nt[r] * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
 
     floatx16 acc[R][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[0][mt][i] = 0.f;
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[r][mt][i] = 0.f;
 
     const int rot = (int)((blockIdx.x * 5u + blockIdx.z * 3u) % (unsigned)nchunks);
     auto chunk_at = [&](int c) {
@@ -150,18 +164,21 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         xdst[i] = seg < XSEG ? m * LDW + sg * 8 : SPARE + tid * 8;
     }
 
-    // the rings are scalars-in-arrays with compile-time indices only
-    uint4 w0[KSTEPS], w1[KSTEPS], w2[KSTEPS], w3[KSTEPS];
-    uint4 x0[XPT], x1[XPT], x2[XPT];
-#define SSD_WSLOT(i) ((i) % DW == 0 ? w0 : (i) % DW == 1 ? w1 : (i) % DW == 2 ? w2 : w3)
-#define SSD_XSLOT(i) ((i) % PX == 0 ? x0 : (i) % PX == 1 ? x1 : x2)
+    // the rings are separate arrays selected by compile-time constants only
+    constexpr int WF = R * KSTEPS;                      // weight fragments per chunk per wave
+    uint4 w0[WF], w1[WF], w2[WF], w3[WF], w4[WF], w5[WF];
+    uint4 x0[XPT], x1[XPT], x2[XPT], x3[XPT];
+#define SSD_WSLOT(i) ((i) % DW == 0 ? w0 : (i) % DW == 1 ? w1 : (i) % DW == 2 ? w2 : (i) % DW == 3 ? w3 : (i) % DW == 4 ? w4 : w5)
+#define SSD_XSLOT(i) ((i) % PX == 0 ? x0 : (i) % PX == 1 ? x1 : (i) % PX == 2 ? x2 : x3)
     auto issue_w = [&](uint4* dst, int c) {
-        const uint4* p = wbase + (size_t)chunk_at(c) * (KC / 16) * 64;
+        const size_t off = (size_t)chunk_at(c) * (KC / 16) * 64;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = p[ks * 64];
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) dst[r * KSTEPS + ks] = wbase[r][off + ks * 64];
     };
     auto issue_x = [&](uint4* dst, int c) {
-        const size_t off = (size_t)chunk_at(c) * KC;
+        const size_t off = (DBG & 8) ? (size_t)0 : (size_t)chunk_at(c) * KC;
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             if (DBG & 2)
@@ -180,7 +197,8 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         }
     };
     // all activation fragments of the chunk are read from LDS first, then the MFMAs run back
-    // to back: one exposed LDS latency per chunk instead of one per MFMA
+    // to back: one exposed LDS latency per chunk instead of one per MFMA; a fragment serves
+    // the wave's R weight tiles
     auto multiply = [&](const uint4* w, int buf) {
         const bf16_t* xb = xs + (size_t)buf * ROWS * LDW + wk * KW + lh * 8;
         bf16x8 xf[KSTEPS][MT];
@@ -190,42 +208,53 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
             for (int mt = 0; mt < MT; ++mt) xf[ks][mt] = *(const bf16x8*)(xb + (size_t)(mt * 32 + lm) * LDW + ks * 16);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            const uint4 wv = w[ks];
+        for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                if (DBG & 1)
-                    acc[0][mt][0] += __uint_as_float(wv.x ^ wv.w) + __uint_as_float(((const uint4*)&xf[ks][mt])->x);
-                else
-                    acc[0][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf[ks][mt], acc[0][mt], 0, 0, 0);
+            for (int r = 0; r < R; ++r) {
+                const uint4 wv = w[r * KSTEPS + ks];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    if (DBG & 1)
+                        acc[r][mt][0] += __uint_as_float(wv.x ^ wv.w) + __uint_as_float(((const uint4*)&xf[ks][mt])->x);
+                    else
+                        acc[r][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf[ks][mt], acc[r][mt], 0, 0, 0);
+                }
             }
-        }
     };
 
+    // Chunk c is multiplied in iteration c from LDS stage c % 3.  Its activations were written
+    // to LDS in iteration c-2, before that iteration's MFMAs, so the write -> barrier -> read
+    // chain of a chunk overlaps the arithmetic of the two chunks before it instead of sitting
+    // between them.  A stage is rewritten in the iteration after its last read; the barrier
+    // that ends every iteration separates the two.
     static_for<0, PX>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_x(SSD_XSLOT(u), u); });
     static_for<0, DW - 1>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_w(SSD_WSLOT(u), u); });
     stage_x(x0, 0);
+    stage_x(x1, 1);
     __syncthreads();
     if constexpr (NCH > 0) {
         static_for<0, NCH>([&](auto ic) {
             constexpr int c = decltype(ic)::value;
+            if constexpr (c + 2 < NCH) stage_x(SSD_XSLOT(c + 2), (c + 2) % NST);
+            __builtin_amdgcn_sched_barrier(0);
             if constexpr (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
             if constexpr (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
-            multiply(SSD_WSLOT(c), c & 1);
-            if constexpr (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
+            multiply(SSD_WSLOT(c), c % NST);
             __syncthreads();
         });
     } else {
-        constexpr int UN = DW * PX;                     // ring slots repeat with this period
+        constexpr int UN = 12;                          // ring and stage slots repeat with this period
+        static_assert(UN % DW == 0 && UN % PX == 0 && UN % NST == 0, "unroll period");
         for (int c0 = 0; c0 < nchunks; c0 += UN) {
             static_for<0, UN>([&](auto ic) {
                 constexpr int u = decltype(ic)::value;
                 const int c = c0 + u;
                 if (c < nchunks) {
+                    stage_x(SSD_XSLOT(u + 2), (u + 2) % NST);
+                    __builtin_amdgcn_sched_barrier(0);
                     issue_x(SSD_XSLOT(u + PX), c + PX);
                     issue_w(SSD_WSLOT(u + DW - 1), c + DW - 1);
-                    multiply(SSD_WSLOT(u), u & 1);
-                    stage_x(SSD_XSLOT(u + 1), (u + 1) & 1);
+                    multiply(SSD_WSLOT(u), u % NST);
                     __syncthreads();
                 }
             });
@@ -236,9 +265,11 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
     if (DBG & 4) {
         float sum = 0.f;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sum += acc[0][mt][i];
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum += acc[r][mt][i];
         if (sum == 1.2345f) *(float*)outv = sum;
         return;
     }
@@ -251,9 +282,310 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         if (!lead) {
             float* dst = red + ((size_t)((wk - 1) * WN + wn) * VALS) * 64 + lane;
 #pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dst[((r * MT + mt) * 16 + i) * 64] = acc[r][mt][i];
+        }
+        __syncthreads();
+        if (lead) {
+#pragma unroll
+            for (int w2 = 1; w2 < WK; ++w2) {
+                const float* src = red + ((size_t)((w2 - 1) * WN + wn) * VALS) * 64 + lane;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[r][mt][i] += src[((r * MT + mt) * 16 + i) * 64];
+            }
+        }
+    }
+
+    // ---- epilogues.  Lane (lm, lh) holds, per tile, rows n = 8*(i/4) + 4*lh + i%4 of column m = lm.
+    if (EPI == EPI_F32) {
+        float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (!lead || !nt_ok[r]) continue;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int m = m0 + mt * 32 + lm;
+                if (m >= M) continue;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nt[r] * 32 + g * 8 + lh * 4;
+                    *(float4*)(out + (size_t)m * N + n) =
+                        make_float4(acc[r][mt][g * 4], acc[r][mt][g * 4 + 1], acc[r][mt][g * 4 + 2], acc[r][mt][g * 4 + 3]);
+                }
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        bf16_t* out = (bf16_t*)outv;
+        if constexpr (R == 2) {
+            // gate (r = 0) and up (r = 1) of the same channels sit in the same lane
+            if (lead && nt_ok[0]) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = m0 + mt * 32 + lm;
+                    if (m >= M) continue;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int f = nt[0] * 32 + g * 8 + lh * 4;
+                        uint16_t o[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float gv = acc[0][mt][g * 4 + j], uv = acc[R - 1][mt][g * 4 + j];
+                            o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
+                        }
+                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
+                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                    }
+                }
+            }
+        } else {
+            // the up wave hands its tile to the gate wave of the same channels through LDS
+            float* xch = (float*)smem_u4;               // [WN/2][MT*16][64]
+            if (WK > 1) __syncthreads();                // the k-slice reduction has finished reading
+            if (lead && (wn & 1)) {
+                float* dst = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[0][mt][i];
+            }
+            __syncthreads();
+            if (lead && !(wn & 1) && nt_ok[0]) {
+                const float* src = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = m0 + mt * 32 + lm;
+                    if (m >= M) continue;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int f = nt[0] * 32 + g * 8 + lh * 4;
+                        uint16_t o[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float gv = acc[0][mt][g * 4 + j], uv = src[(mt * 16 + g * 4 + j) * 64];
+                            o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
+                        }
+                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
+                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                    }
+                }
+            }
+        }
+    } else if (lead) {
+        // LM head: per (row, n-tile) partial over the tile's 32 vocabulary rows
+        float* out = (float*)outv;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int tile_out = (blockIdx.x * WN + wn) * R + r;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                float bm = -INFINITY;
+                int bi = 0x7fffffff;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int n = nt[r] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                    const float v = acc[r][mt][i];
+                    if (n != mask_id && v > bm) { bm = v; bi = n; }
+                }
+                {
+                    const float om = __shfl_xor(bm, 32, 64);
+                    const int oi = __shfl_xor(bi, 32, 64);
+                    if (om > bm || (om == bm && oi < bi)) { bm = om; bi = oi; }
+                }
+                float se = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int n = nt[r] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                    if (n != mask_id) se += expf(acc[r][mt][i] - bm);
+                }
+                se += __shfl_xor(se, 32, 64);
+                const int m = m0 + mt * 32 + lm;
+                if (lh == 0 && m < M && tile_out < n_tiles_out && nt_ok[r]) {
+                    float* o = out + ((size_t)m * n_tiles_out + tile_out) * 3;
+                    o[0] = bm;
+                    o[1] = __int_as_float(bi);
+                    o[2] = se;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------
+// GEMM, producer/consumer form.  Loads complete in issue order within a wave, so a wave that
+// both keeps a deep queue of HBM weight loads in flight and has to wait for an activation load
+// every chunk ends up waiting for its weight queue.  Here the two streams live in different
+// waves: WN*WK consumer waves stream weights into registers and run the MFMAs, NP producer
+// waves do nothing but move activation chunks global -> registers -> LDS.  One barrier per
+// chunk joins them.  Everything else (tiling, rotation, epilogues) is as in k_gemm_mfma.
+// ------------------------------------------------------------------------
+template <int WN, int WK, int NP, int MT, int EPI, int NCH, int DBG = 0, int DW = 3, int PX = 2, int KSTEPS = 2>
+__global__ __launch_bounds__((WN * WK + NP) * 64) void k_gemm_pc(const bf16_t* X, const uint4* Wp, void* outv, int M,
+                                                                 int N, int K, int k_len, size_t split_stride,
+                                                                 int up_tile_off, int mask_id, int n_tiles_out) {
+    constexpr int NC = WN * WK, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
+    constexpr int TP = NP * 64;
+    constexpr int XSEG = ROWS * (KC / 8), XPT = (XSEG + TP - 1) / TP, SPARE = 2 * ROWS * LDW;
+    static_assert(DW >= 2 && DW <= 4 && PX >= 1 && PX <= 3, "ring depths");
+    extern __shared__ uint4 smem_u4[];
+    bf16_t* xs = (bf16_t*)smem_u4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int m0 = blockIdx.y * ROWS;
+    const int kbeg = blockIdx.z * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
+    const int rot = (int)((blockIdx.x * 5u + blockIdx.z * 3u) % (unsigned)nchunks);
+    auto chunk_at = [&](int c) {
+        c = c < nchunks - 1 ? c : nchunks - 1;
+        c += rot;
+        return c >= nchunks ? c - nchunks : c;
+    };
+    if (wave >= NC) {
+        // ------------------------------------------------ producer: activations only
+        const int pt = tid - NC * 64;
+        const bf16_t* xsrc[XPT];
+        int xdst[XPT];
+        bool xok[XPT];
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int seg = pt + i * TP;
+            const int m = seg / (KC / 8), sg = seg - m * (KC / 8);
+            xok[i] = seg < XSEG && m0 + m < M;
+            xsrc[i] = X + (size_t)(xok[i] ? m0 + m : 0) * K + kbeg + sg * 8;
+            xdst[i] = seg < XSEG ? m * LDW + sg * 8 : SPARE + pt * 8;
+        }
+        uint4 x0[XPT], x1[XPT], x2[XPT];
+#define SSD_XSLOT(i) ((i) % PX == 0 ? x0 : (i) % PX == 1 ? x1 : x2)
+        auto issue_x = [&](uint4* dst, int c) {
+            const size_t off = (size_t)chunk_at(c) * KC;
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) dst[i] = *(const uint4*)(xsrc[i] + off);
+        };
+        auto stage_x = [&](const uint4* src, int buf) {
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) {
+                uint4 v = src[i];
+                if (!xok[i]) v = make_uint4(0, 0, 0, 0);
+                const int off = xdst[i] < SPARE ? buf * ROWS * LDW + xdst[i] : xdst[i];
+                *(uint4*)(xs + off) = v;
+            }
+        };
+        static_for<0, PX>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_x(SSD_XSLOT(u), u); });
+        stage_x(x0, 0);
+        __syncthreads();
+        if constexpr (NCH > 0) {
+            static_for<0, NCH>([&](auto ic) {
+                constexpr int c = decltype(ic)::value;
+                if constexpr (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
+                if constexpr (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
+                __syncthreads();
+            });
+        } else {
+            constexpr int UN = 2 * PX;
+            for (int c0 = 0; c0 < nchunks; c0 += UN)
+                static_for<0, UN>([&](auto ic) {
+                    constexpr int u = decltype(ic)::value;
+                    if (c0 + u < nchunks) {
+                        issue_x(SSD_XSLOT(u + PX), c0 + u + PX);
+                        stage_x(SSD_XSLOT(u + 1), (u + 1) & 1);
+                        __syncthreads();
+                    }
+                });
+        }
+#undef SSD_XSLOT
+        if (!(DBG & 4)) {
+            if (WK > 1) __syncthreads();
+            if (EPI == EPI_SWIGLU) { if (WK > 1) __syncthreads(); __syncthreads(); }
+        }
+        return;
+    }
+    // ---------------------------------------------------- consumers: weights + MFMA
+    const int wn = wave % WN, wk = wave / WN;
+    const int lm = lane & 31, lh = lane >> 5;
+    const int KS = K >> 4, NT = N >> 5;
+    int nt0;
+    bool nt_ok0;
+    if (EPI == EPI_SWIGLU) {
+        const int ch = blockIdx.x * (WN / 2) + (wn >> 1);
+        nt_ok0 = ch < up_tile_off;
+        nt0 = (nt_ok0 ? ch : up_tile_off - 1) + ((wn & 1) ? up_tile_off : 0);
+    } else {
+        nt0 = blockIdx.x * WN + wn;
+        nt_ok0 = nt0 < NT;
+        if (!nt_ok0) nt0 = NT - 1;
+    }
+    const uint4* wbase = Wp + ((size_t)nt0 * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
+    floatx16 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
+    uint4 w0[KSTEPS], w1[KSTEPS], w2[KSTEPS], w3[KSTEPS];
+#define SSD_WSLOT(i) ((i) % DW == 0 ? w0 : (i) % DW == 1 ? w1 : (i) % DW == 2 ? w2 : w3)
+    auto issue_w = [&](uint4* dst, int c) {
+        const uint4* p = wbase + (size_t)chunk_at(c) * (KC / 16) * 64;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = p[ks * 64];
+    };
+    auto multiply = [&](const uint4* w, int buf) {
+        const bf16_t* xb = xs + (size_t)buf * ROWS * LDW + wk * KW + lh * 8;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            bf16x8 xf[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xf[mt] = *(const bf16x8*)(xb + (size_t)(mt * 32 + lm) * LDW + ks * 16);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint4 wv = w[ks];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf[mt], acc[mt], 0, 0, 0);
+        }
+    };
+    static_for<0, DW - 1>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_w(SSD_WSLOT(u), u); });
+    __syncthreads();
+    if constexpr (NCH > 0) {
+        static_for<0, NCH>([&](auto ic) {
+            constexpr int c = decltype(ic)::value;
+            if constexpr (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
+            multiply(SSD_WSLOT(c), c & 1);
+            __syncthreads();
+        });
+    } else {
+        constexpr int UN = 2 * DW;
+        for (int c0 = 0; c0 < nchunks; c0 += UN)
+            static_for<0, UN>([&](auto ic) {
+                constexpr int u = decltype(ic)::value;
+                if (c0 + u < nchunks) {
+                    issue_w(SSD_WSLOT(u + DW - 1), c0 + u + DW - 1);
+                    multiply(SSD_WSLOT(u), u & 1);
+                    __syncthreads();
+                }
+            });
+    }
+#undef SSD_WSLOT
+    if (DBG & 4) {
+        float sum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += acc[mt][i];
+        if (sum == 1.2345f) *(float*)outv = sum;
+        return;
+    }
+    const bool lead = wk == 0;
+    if (WK > 1) {
+        float* red = (float*)smem_u4;
+        constexpr int VALS = MT * 16;
+        if (!lead) {
+            float* dst = red + ((size_t)((wk - 1) * WN + wn) * VALS) * 64 + lane;
+#pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[0][mt][i];
+                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[mt][i];
         }
         __syncthreads();
         if (lead) {
@@ -263,41 +595,38 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[0][mt][i] += src[(mt * 16 + i) * 64];
+                    for (int i = 0; i < 16; ++i) acc[mt][i] += src[(mt * 16 + i) * 64];
             }
         }
     }
-
-    // ---- epilogues.  Lane (lm, lh) holds, per tile, rows n = 8*(i/4) + 4*lh + i%4 of column m = lm.
     if (EPI == EPI_F32) {
         float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
-        if (lead && nt_ok[0]) {
+        if (lead && nt_ok0) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int m = m0 + mt * 32 + lm;
                 if (m >= M) continue;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = nt[0] * 32 + g * 8 + lh * 4;
+                    const int n = nt0 * 32 + g * 8 + lh * 4;
                     *(float4*)(out + (size_t)m * N + n) =
-                        make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
+                        make_float4(acc[mt][g * 4], acc[mt][g * 4 + 1], acc[mt][g * 4 + 2], acc[mt][g * 4 + 3]);
                 }
             }
         }
     } else if (EPI == EPI_SWIGLU) {
-        // the up wave hands its tile to the gate wave of the same channels through LDS
-        float* xch = (float*)smem_u4;                   // [WN/2][MT*16][64]
-        if (WK > 1) __syncthreads();                    // the k-slice reduction has finished reading
+        float* xch = (float*)smem_u4;
+        if (WK > 1) __syncthreads();
         if (lead && (wn & 1)) {
             float* dst = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[0][mt][i];
+                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[mt][i];
         }
         __syncthreads();
         bf16_t* out = (bf16_t*)outv;
-        if (lead && !(wn & 1) && nt_ok[0]) {
+        if (lead && !(wn & 1) && nt_ok0) {
             const float* src = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
@@ -305,11 +634,11 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
                 if (m >= M) continue;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int f = nt[0] * 32 + g * 8 + lh * 4;
+                    const int f = nt0 * 32 + g * 8 + lh * 4;
                     uint16_t o[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float gv = acc[0][mt][g * 4 + j], uv = src[(mt * 16 + g * 4 + j) * 64];
+                        const float gv = acc[mt][g * 4 + j], uv = src[(mt * 16 + g * 4 + j) * 64];
                         o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
                     }
                     *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
@@ -318,7 +647,6 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
             }
         }
     } else if (lead) {
-        // LM head: per (row, wave) partial over the wave's 32 vocabulary rows
         float* out = (float*)outv;
         const int tile_out = blockIdx.x * WN + wn;
 #pragma unroll
@@ -327,8 +655,8 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
             int bi = 0x7fffffff;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int n = nt[0] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                const float v = acc[0][mt][i];
+                const int n = nt0 * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                const float v = acc[mt][i];
                 if (n != mask_id && v > bm) { bm = v; bi = n; }
             }
             {
@@ -339,12 +667,12 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
             float se = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int n = nt[0] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                if (n != mask_id) se += expf(acc[0][mt][i] - bm);
+                const int n = nt0 * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
+                if (n != mask_id) se += expf(acc[mt][i] - bm);
             }
             se += __shfl_xor(se, 32, 64);
             const int m = m0 + mt * 32 + lm;
-            if (lh == 0 && m < M && tile_out < n_tiles_out && nt_ok[0]) {
+            if (lh == 0 && m < M && tile_out < n_tiles_out && nt_ok0) {
                 float* o = out + ((size_t)m * n_tiles_out + tile_out) * 3;
                 o[0] = bm;
                 o[1] = __int_as_float(bi);
@@ -362,15 +690,15 @@ static int env_int(const char* name, int dflt) {
     return s ? atoi(s) : dflt;
 }
 
-template <int WN, int WK, int MT, int EPI, int NCH>
+template <int WN, int WK, int R, int MT, int EPI, int NCH>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
                        int up_tile_off, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
     constexpr int KC = WK * 32, ROWS = MT * 32, LDW = KC + 8;
-    constexpr size_t xbytes = (size_t)2 * ROWS * LDW * 2 + (size_t)WN * WK * 64 * 16;   // two stages + spare slots
-    constexpr size_t rbytes = WK > 1 ? (size_t)(WK - 1) * WN * MT * 16 * 64 * 4 : (size_t)(WN / 2) * MT * 16 * 64 * 4;
+    constexpr size_t xbytes = (size_t)3 * ROWS * LDW * 2 + (size_t)WN * WK * 64 * 16;   // three stages + spare slots
+    constexpr size_t rbytes = WK > 1 ? (size_t)(WK - 1) * WN * R * MT * 16 * 64 * 4 : (size_t)(WN / 2 + 1) * MT * 16 * 64 * 4;
     constexpr size_t smem = xbytes > rbytes ? xbytes : rbytes;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = k_gemm_mfma<WN, WK, MT, EPI, NCH>;
+    auto kern = k_gemm_mfma<WN, WK, R, MT, EPI, NCH>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -378,7 +706,7 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
         attr_done = true;
     }
     const int tiles = EPI == EPI_SWIGLU ? up_tile_off : N / 32;
-    const int per_wg = EPI == EPI_SWIGLU ? WN / 2 : WN;
+    const int per_wg = EPI == EPI_SWIGLU ? (R == 2 ? WN : WN / 2) : WN * R;
     dim3 grid((tiles + per_wg - 1) / per_wg, m_chunks, split);
     hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K / split, split_stride,
                        up_tile_off, mask_id, n_tiles_out);
@@ -387,13 +715,13 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
 
 // Row tiles per pass: 1 (a stepwise forward of one block), 2, or 5 (a 5-node tree);
 // other row counts round up (padding rows are zero and never stored).
-template <int WN, int WK, int EPI, int NCH>
+template <int WN, int WK, int R, int EPI, int NCH>
 static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
                       size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
                       hipStream_t st) {
 #define SSD_MT_CASE(v)                                                                                          \
     case v:                                                                                                     \
-        return launch_one<WN, WK, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,  \
+        return launch_one<WN, WK, R, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,  \
                                                n_tiles_out, m_chunks, st);
     switch (mt) {
         SSD_MT_CASE(1)
@@ -405,13 +733,13 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
 }
 
 // Chunk counts with a straight-line kernel; anything else takes the looped one (NCH = 0).
-template <int WN, int WK, int EPI>
+template <int WN, int WK, int R, int EPI>
 static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
                        size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
                        hipStream_t st) {
 #define SSD_NCH_CASE(v)                                                                                           \
     case v:                                                                                                       \
-        return launch_mt<WN, WK, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,      \
+        return launch_mt<WN, WK, R, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,      \
                                          n_tiles_out, m_chunks, st);
     if (EPI == EPI_F32) {
         switch (nch) {
@@ -425,7 +753,7 @@ static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* 
         switch (nch) { SSD_NCH_CASE(64) }
     }
 #undef SSD_NCH_CASE
-    return launch_mt<WN, WK, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id, n_tiles_out,
+    return launch_mt<WN, WK, R, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id, n_tiles_out,
                                      m_chunks, st);
 }
 
@@ -456,17 +784,17 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
         const int F = N / 2;
         if (F % 32) return false;
         *n_split = 1;
-        return launch_nch<WN, WK, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, F, K, 1, 0, F / 32, -1, 0, m_chunks, st);
+        return launch_nch<WN, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, F, K, 1, 0, F / 32, -1, 0, m_chunks, st);
     }
     if (epi == EPI_LMHEAD) {
         *n_split = lm_tiles_mfma(N);
-        return launch_nch<WN, WK, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
+        return launch_nch<WN, WK, 1, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
     }
     int want = N <= 8192 ? env_int("SSD_SPLIT_SMALLN", 8) : env_int("SSD_SPLIT_LARGEN", 2);
     if (want > SSD_MAX_SPLIT) want = SSD_MAX_SPLIT;
     const int split = pick_split(K, KC, want);
     *n_split = split;
-    return launch_nch<WN, WK, EPI_F32>(K / split / KC, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    return launch_nch<WN, WK, 1, EPI_F32>(K / split / KC, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
 }
 #endif
 

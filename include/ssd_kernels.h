@@ -1,0 +1,39 @@
+/*
+ * ssd_kernels.h - kernel-level entry points of the SSD library, for unit
+ * parity tests and measurement.  They run exactly the kernels the forward
+ * (ssd.h) runs for one step of Section 3.1's transformer f_theta, on operands
+ * the caller supplies, so a single step can be checked against a definition
+ * with nothing upstream to blur it.
+ */
+#ifndef SSD_KERNELS_H
+#define SSD_KERNELS_H
+
+#include "ssd.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SSD_LIN_QKV  0   /* x [M, d_model]      -> out fp32 [M, (Hq+2Hkv)*dh]                  */
+#define SSD_LIN_O    1   /* x [M, Hq*dh]        -> out fp32 [M, d_model]                        */
+#define SSD_LIN_GU   2   /* x [M, d_model]      -> out cfg.dtype [M, d_ffn] = silu(gate)*up     */
+#define SSD_LIN_DOWN 3   /* x [M, d_ffn]        -> out fp32 [M, d_model]                        */
+#define SSD_LIN_LM   4   /* x [M, d_model]      -> out fp32 [3, M]: max logit, arg-max (as float), confidence */
+
+/* One linear step of layer `layer` (ignored for SSD_LIN_LM) with the kernel path the context
+ * currently selects: x and out are device pointers, x in cfg.dtype, row-major, M <= max_rows.
+ * Split-K partial sums are added in split order, as the forward's consumers do.
+ * Asynchronous on the context's stream.  Errors: SSD_EINVAL, SSD_ERANGE. */
+int ssd_k_linear(ssd_ctx* ctx, int which, int layer, const void* x, int M, void* out);
+
+/* Streams `bytes` of device memory with the access pattern of the GEMM's weight stream
+ * (work_groups x waves_per_wg waves, `depth` 16-byte loads in flight per lane: 4, 8 or 16):
+ * the HBM read rate the chip sustains, i.e. the practical ceiling of the roofline.
+ * `sink` is 16 bytes of device scratch.  Asynchronous on `hip_stream`. */
+int ssd_debug_stream_read(const void* src, size_t bytes, int work_groups, int waves_per_wg, int depth,
+                          void* sink, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_KERNELS_H */

@@ -20,7 +20,9 @@ SSD_F32, SSD_BF16 = 0, 1
 
 EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd_cached_len", "ssd_prefill_kv",
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_profile_begin",
-           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error"]
+           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear",
+           "ssd_debug_stream_read"]
+LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
 
 class SsdConfig(C.Structure):
@@ -74,6 +76,8 @@ def load_library() -> C.CDLL:
         getattr(lib, n).argtypes = [C.c_void_p]
     lib.ssd_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
+    lib.ssd_k_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    lib.ssd_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     lib.ssd_strerror.restype = C.c_char_p
     lib.ssd_strerror.argtypes = [C.c_int]
     lib.ssd_last_error.restype = C.c_char_p
@@ -250,6 +254,11 @@ class SSD:
                      accept_hist=list(st.accept_hist), decode_ms=st.decode_ms, kv_ms=st.kv_ms,
                      total_ms=st.total_ms)
         return out, stats
+
+    def k_linear(self, which, layer, x, out):
+        """One linear step on caller-supplied rows x [M, K] (device tensor of the model dtype)."""
+        assert x.is_contiguous() and out.is_contiguous() and x.device == self.device
+        self._chk(self.lib.ssd_k_linear(self.h, which, layer, x.data_ptr(), x.shape[0], out.data_ptr()))
 
     def profile_begin(self):
         self._chk(self.lib.ssd_profile_begin(self.h))

@@ -648,3 +648,28 @@ void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipS
     k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result, o,
                                       c->dm.block, c->dm.max_draft);
 }
+
+// Helpers of the kernel-level entry points.
+__global__ void k_sum_partials(const float* __restrict__ part, int n_part, size_t part_stride, float* __restrict__ out,
+                               size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float v = part[i];
+    for (int s = 1; s < n_part; ++s) v += part[s * part_stride + i];
+    out[i] = v;
+}
+
+__global__ void k_int_to_float(const int* __restrict__ src, float* __restrict__ dst, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = (float)src[i];
+}
+
+void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out, hipStream_t st) {
+    const size_t n = (size_t)M * N;
+    k_sum_partials<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(c->b.part, n_part,
+                                                                (size_t)c->dm.max_rows * c->part_cols, out, n);
+}
+
+void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st) {
+    k_int_to_float<<<(n + 255) / 256, 256, 0, st>>>(src, dst, n);
+}

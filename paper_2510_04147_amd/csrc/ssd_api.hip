@@ -11,6 +11,7 @@
 #include <new>
 
 #include "ssd_internal.h"
+#include "../../include/ssd_kernels.h"
 
 #define HIPCHK(ctx, call)                                                                   \
     do {                                                                                    \
@@ -622,4 +623,43 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
     sta.total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     if (stats) *stats = sta;
     return done(SSD_OK);
+}
+
+// ---------------------------------------------------------- kernel-level entry
+extern "C" __attribute__((visibility("default"))) int ssd_k_linear(ssd_ctx* c, int which, int layer, const void* x,
+                                                                   int M, void* out) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!x || !out || M < 1) { set_err(c, "k_linear: null pointer or M < 1"); return SSD_EINVAL; }
+    if (M > d.max_rows) { set_err(c, "k_linear: M exceeds max_rows"); return SSD_ERANGE; }
+    if (which != SSD_LIN_LM && (layer < 0 || layer >= d.L)) { set_err(c, "k_linear: layer out of range"); return SSD_ERANGE; }
+    int ns = 1;
+    switch (which) {
+        case SSD_LIN_QKV:
+        case SSD_LIN_O:
+        case SSD_LIN_DOWN: {
+            const LayerW& w = c->lw[layer];
+            const Wt& W = which == SSD_LIN_QKV ? w.wqkv : which == SSD_LIN_O ? w.wo : w.wdown;
+            gemm(c, KC_GEMM_QKV, EPI_F32, x, W, c->b.part, M, &ns);
+            launch_sum_partials(c, M, W.N, ns, (float*)out, c->stream);
+            break;
+        }
+        case SSD_LIN_GU:
+            gemm(c, KC_GEMM_GU, EPI_SWIGLU, x, c->lw[layer].wgu, out, M, &ns);
+            break;
+        case SSD_LIN_LM: {
+            int tiles = 0;
+            gemm(c, KC_LMHEAD, EPI_LMHEAD, x, c->lm_head, c->b.lm_part, M, &tiles);
+            launch_lm_merge(c, M, tiles, c->stream);
+            HIPCHK(c, hipMemcpyAsync(out, c->b.row_max, (size_t)M * 4, hipMemcpyDeviceToDevice, c->stream));
+            launch_int_to_float(c->b.row_arg, (float*)out + M, M, c->stream);
+            HIPCHK(c, hipMemcpyAsync((float*)out + 2 * (size_t)M, c->b.row_conf, (size_t)M * 4, hipMemcpyDeviceToDevice, c->stream));
+            break;
+        }
+        default:
+            set_err(c, "k_linear: unknown step %d", which);
+            return SSD_EINVAL;
+    }
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
 }

@@ -165,6 +165,9 @@ void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
 void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st);
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);
 int lm_tiles_plain(int V);
+// out[M,N] = sum over the first n_part split-K partial buffers, in split order
+void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out, hipStream_t st);
+void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st);
 
 enum GemmEpi : int { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
 // out[M,N] = X[M,K] * W[N,K]^T with the plain FMA kernel.

@@ -1,6 +1,13 @@
-"""GPU parity for bf16 models with the 8B-class layer shape (d=4096, 32x128 heads,
-FFN 12288, vocab 126464): MFMA kernels against the fp32 CPU oracle (teacher forced),
-against the plain FMA kernels, and GPU SSD == GPU stepwise bit for bit."""
+"""GPU parity for bf16 models of the 8B-class layer shape (d=4096, 32x128 heads, FFN 12288,
+vocab 126464), two layers deep so the CPU oracle finishes in seconds:
+
+  * every linear step (QKV, O, gate/up+SwiGLU, down, LM-head reduction) on its own, MFMA kernels
+    against an fp64 product of the same bf16 operands: tight, nothing upstream to blur it;
+  * whole forwards, teacher forced from the oracle's state, against the exact fp32 oracle with
+    tolerances derived from the operand noise floor (parity_util.operand_noise_floor);
+  * GPU SSD == GPU stepwise bit for bit, one- and multi-sequence, and a node's rows bit-identical
+    whether computed alone or inside a 5-node forward.
+"""
 import numpy as np
 import pytest
 import torch
@@ -11,9 +18,6 @@ from parity_util import bits
 
 pytestmark = pytest.mark.gpu
 
-# bf16 GEMM operands, fp32 accumulation and residual, against the fp32 oracle
-TOL = dict(maxlogit_tol=2e-2, margin_tol=1e-2, conf_tol=5e-2, conf_rtol=5e-2)
-
 
 @pytest.fixture(scope="module")
 def shallow8b():
@@ -23,35 +27,77 @@ def shallow8b():
     wg = synth.gen_weights(cfg, 0, device="cuda")
     w = synth.weights_to(wg, "cpu")
     eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=512, block=32, max_draft=4, max_rows=320)
-    yield cfg, w, wg, eng
+    prompt = synth.gen_prompt(cfg, 1002, 100)          # prefix length not a multiple of any tile
+    sigma = parity_util.operand_noise_floor(cfg, w, prompt, 32, torch.float32)
+    print(f"operand noise floor sigma = {sigma:.4f}")
+    yield cfg, w, wg, eng, prompt, sigma
     eng.close()
 
 
-def test_mfma_path_teacher_forced_against_oracle(shallow8b):
-    cfg, w, wg, eng = shallow8b
-    prompt = synth.gen_prompt(cfg, 1002, 100)          # prefix length not a multiple of any tile
+@pytest.mark.parametrize("M", [160, 32, 45])
+def test_linear_steps_against_fp64_products(shallow8b, M):
+    """Each GEMM kernel alone: bf16 operands, fp32 accumulation, against fp64 on the same operands."""
+    from paper_2510_04147_amd import binding as B
+    cfg, w, wg, eng, _, _ = shallow8b
+    d, F, V = cfg["d_model"], cfg["d_ffn"], cfg["vocab"]
+    g = torch.Generator(device="cuda").manual_seed(5 + M)
+    lw, lwc = wg["layers"][1], w["layers"][1]
+    for path in (1, 0):
+        eng.set_kernel_path(path)
+        for which, W, K, N in ((B.LIN_QKV, lwc["wqkv"], d, 3 * d), (B.LIN_O, lwc["wo"], d, d), (B.LIN_DOWN, lwc["wdown"], F, d)):
+            x = torch.randn(M, K, generator=g, device="cuda").to(torch.bfloat16)
+            out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+            eng.k_linear(which, 1, x, out)
+            want = x.cpu().double() @ W.double().T
+            err = (out.cpu().double() - want).abs().max().item()
+            assert err < 2e-4 * max(1.0, (K / 4096) ** 0.5), (path, which, err)
+        x = torch.randn(M, d, generator=g, device="cuda").to(torch.bfloat16)
+        out = torch.empty(M, F, dtype=torch.bfloat16, device="cuda")
+        eng.k_linear(B.LIN_GU, 1, x, out)
+        gu = x.cpu().double() @ lwc["wgu"].double().T
+        want = gu[:, :F] / (1 + torch.exp(-gu[:, :F])) * gu[:, F:]
+        diff = (out.cpu().double() - want).abs()
+        assert bool((diff <= 2.0 ** -8 * want.abs() + 1e-4).all()), (path, diff.max())     # one bf16 rounding
+        # LM head: max logit, arg-max and confidence without ever writing the logits
+        x = torch.randn(M, d, generator=g, device="cuda").to(torch.bfloat16)
+        out = torch.empty(3, M, dtype=torch.float32, device="cuda")
+        eng.k_linear(B.LIN_LM, 0, x, out)
+        lg = x.cpu().double() @ w["lm_head"].double().T
+        lg[:, cfg["mask_id"]] = float("-inf")
+        m, t = lg.max(dim=-1)
+        c = 1.0 / torch.exp(lg - m[:, None]).sum(-1)
+        o = out.cpu().double()
+        assert (o[0] - m).abs().max() < 2e-4
+        assert torch.equal(o[1].long(), t)
+        assert ((o[2] - c).abs() <= 1e-4 * c).all()
     eng.set_kernel_path(1)
-    ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 32, 32, 4, torch.float32, **TOL)
-    print("mfma totals:", tot)
+
+
+def test_mfma_path_teacher_forced_against_oracle(shallow8b):
+    cfg, w, wg, eng, prompt, sigma = shallow8b
+    eng.set_kernel_path(1)
+    tol = parity_util.bf16_tolerances(sigma)
+    ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 32, 32, 4, torch.float32, **tol)
+    print("mfma totals:", tot, "sigma", sigma)
     assert tot["forwards"] == st["forwards"] and tot["rows"] > 200
-    assert tot["tok_exempt"] <= 0.05 * tot["rows"]
+    assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3, "GPU deviates from the exact oracle by more than bf16 operands explain"
+    assert tot["tok_exempt"] <= 0.10 * tot["rows"]
 
 
 def test_plain_path_teacher_forced_against_oracle(shallow8b):
-    cfg, w, wg, eng = shallow8b
-    prompt = synth.gen_prompt(cfg, 1002, 100)
+    cfg, w, wg, eng, prompt, sigma = shallow8b
     eng.set_kernel_path(0)
     try:
-        ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 32, 32, 4, torch.float32, max_blocks=1, **TOL)
+        tol = parity_util.bf16_tolerances(sigma)
+        ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 32, 32, 4, torch.float32, max_forwards=4, **tol)
     finally:
         eng.set_kernel_path(1)
     print("plain totals:", tot)
-    assert tot["forwards"] == st["forwards"]
+    assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
 
 
 def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
-    cfg, w, wg, eng = shallow8b
-    prompt = synth.gen_prompt(cfg, 1002, 100)
+    cfg, w, wg, eng, prompt, _ = shallow8b
     base, s0 = eng.generate([prompt], 64, 32, 0)
     assert s0["forwards"] == 64
     for N in (1, 4):
@@ -67,7 +113,7 @@ def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
 
 def test_node_rows_independent_of_batch_shape(shallow8b):
     """A node's rows are bit-identical alone (M=32) and inside a 5-node forward (M=160)."""
-    cfg, w, wg, eng = shallow8b
+    cfg, w, wg, eng, _, _ = shallow8b
     prompt = synth.gen_prompt(cfg, 5, 75)
     eng.reset(0)
     eng.prefill_kv(0, prompt, 0)

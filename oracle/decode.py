@@ -149,10 +149,12 @@ def stepwise(w, cfg, prompt, gen_len, block, dtype=torch.float64, trace=None, ma
     return out, dict(forwards=forwards, kv_passes=kv_passes)
 
 
-def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None, max_blocks=None):
+def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None, max_blocks=None,
+        max_forwards=None):
     """Self Speculative Decoding with draft length n_draft (Algorithm 1).
     Returns (tokens, stats) with stats['accept_hist'][a] = number of forwards
-    that accepted a tokens."""
+    that accepted a tokens.  max_blocks / max_forwards stop early (the tokens
+    returned are then a prefix; used to sample forwards of large models)."""
     P = len(prompt)
     cache = _prefill(w, cfg, prompt, dtype)
     out, forwards, kv_passes = [], 0, 1
@@ -164,6 +166,8 @@ def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None
         tok, masked = [cfg["mask_id"]] * Bj, [True] * Bj
         drafts = []            # the block-start self-draft is a chain with no drafts
         while any(masked):
+            if max_forwards is not None and forwards >= max_forwards:
+                return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
             nodes = build_chain(tok, masked, drafts)
             # one batched forward over all nodes (Eq. 5); nodes do not see each other
             preds = [_node_forward(w, cfg, nt, S, cache, dtype) for (nt, _) in nodes]

@@ -131,7 +131,8 @@ def teacher_forced(eng, cfg, w, prompt, gen_len, block, N, dtype, max_blocks=Non
     recorded forward through the HIP entry points from the oracle's state and
     compares.  Returns (oracle tokens, oracle stats, totals)."""
     trace = []
-    ref, st = decode.ssd(w, cfg, prompt, gen_len, block, N, dtype=dtype, trace=trace, max_blocks=max_blocks)
+    ref, st = decode.ssd(w, cfg, prompt, gen_len, block, N, dtype=dtype, trace=trace, max_blocks=max_blocks,
+                         max_forwards=max_forwards)
     eng.reset(seq)
     eng.prefill_kv(seq, prompt, 0)
     out = eng.new_out(1)

@@ -1,0 +1,38 @@
+"""The benchmark configuration at full size (32 layers of the 8B shape, prompt 256, block 32,
+draft depth 4) in the launch configuration bench.py times: GPU SSD == GPU stepwise bit for bit
+over two blocks, and sampled forwards (the block-start draft and the first verification forward)
+against the exact fp32 oracle, which computes them one by one in about a minute."""
+import numpy as np
+import pytest
+import torch
+
+import parity_util
+from paper_2510_04147_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg2_full_depth():
+    from paper_2510_04147_amd import binding
+    wl = synth.WORKLOADS["cfg2_8b_b32_n4"]
+    cfg = synth.model_config(wl["model"])
+    wg = synth.gen_weights(cfg, 0, device="cuda")
+    B, N, P = wl["block"], wl["draft"], wl["prompt_len"]
+    eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=P + 256, block=B, max_draft=N, max_rows=max(P, (N + 1) * B))
+    prompt = synth.gen_prompt(cfg, wl["seed"], P)
+    print("generate: stepwise and SSD, two blocks", flush=True)
+    base, s0 = eng.generate([prompt], 2 * B, B, 0)
+    out, s4 = eng.generate([prompt], 2 * B, B, N)
+    assert np.array_equal(out, base), "GPU SSD differs from GPU stepwise at full depth"
+    assert s0["forwards"] == 2 * B and s4["forwards"] <= 2 * B
+    print("accept_hist", s4["accept_hist"][:N + 2], flush=True)
+    print("copying weights to the host for the oracle", flush=True)
+    w = synth.weights_to(wg, "cpu")
+    print("oracle: operand noise floor (4 layer-stack passes)", flush=True)
+    sigma = parity_util.operand_noise_floor(cfg, w, prompt, B, torch.float32)
+    tol = parity_util.bf16_tolerances(sigma)
+    print(f"sigma = {sigma:.4f}; oracle SSD for two forwards", flush=True)
+    _, _, tot = parity_util.teacher_forced(eng, cfg, w, prompt, B, B, N, torch.float32, max_forwards=2, **tol)
+    print("full-size totals", tot, flush=True)
+    assert tot["rows"] >= 32 and tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
+    eng.close()

@@ -28,6 +28,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
+def read_measured_traffic(workload):
+    """HBM bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"gemm_gate_up_{workload}_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +51,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-generate", action="store_true")
     ap.add_argument("--prefix", type=int, default=384)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy, the known-size kernel that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -93,6 +109,33 @@ def main():
         wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         ms_step = e0.elapsed_time(e1) / args.steps
 
+        if args.copy_calibration:
+            a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            b = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            b.copy_(a)
+            stream.synchronize()
+            del a, b
+
+        # ---- what this chip sustains for a pure streaming read of HBM-resident data (the weight
+        # stream's access pattern, 2 GiB so the 256 MB Infinity Cache cannot serve it)
+        note("streaming-read ceiling")
+        big = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+        big.zero_()
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        stream.synchronize()
+        ceil_gbs = 0.0
+        for wgs, depth in ((256, 8), (512, 8), (1024, 16)):
+            for _ in range(2):
+                eng.lib.ssd_debug_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record(stream)
+            for _ in range(5):
+                eng.lib.ssd_debug_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
+            c1.record(stream)
+            stream.synchronize()
+            ceil_gbs = max(ceil_gbs, big.numel() * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9)
+        del big
+
         # ---- per-kernel-class timing (HIP events on the same stream, separate pass)
         note(f"{ms_step:.3f} ms per forward; per-kernel event timing")
         eng.profile_begin()
@@ -130,6 +173,7 @@ def main():
     gu_bytes = 2 * F * d * esz + M * d * esz + M * F * esz     # weights + activations in + SwiGLU out
     gu_us = 1e3 * gu["ms"] / max(gu["launches"], 1)
     gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9 if gu_us > 0 else 0.0
+    traffic = read_measured_traffic(args.workload)
     line = {
         "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
         "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -139,9 +183,10 @@ def main():
                    "prompt_len": P, "gen_len": G, "block": B, "draft_depth": N, "rows_per_forward": M,
                    "prefix_len_timed": S},
         "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"]},
         "forward": {"bytes_per_forward": bytes_fwd, "achieved_GBs": fwd_gbs, "frac_of_hbm_peak": fwd_gbs / HBM_PEAK_GBS,
+                    "hbm_streaming_read_ceiling_GBs": ceil_gbs, "frac_of_streaming_ceiling": fwd_gbs / ceil_gbs,
                     "host_wall_ms_per_step": wall_ms,
                     "kernel_classes_us_per_forward": {k: 1e3 * v["ms"] / n_prof for k, v in prof.items()}},
         "generate": gen,

@@ -146,8 +146,8 @@ int ssd_prefill_kv(ssd_ctx* ctx, int seq, const int32_t* tokens, int n, int pos0
 /* Self-draft (Section 3.2.2, Eq. 4; Algorithm 1 line 4): a one-node forward for
  * each listed sequence on its current block.  Accepts the stepwise choice (most
  * confident masked position) and returns up to n_draft_next drafts, the other
- * masked positions by descending confidence (at most #masked-2 of them ... see
- * ssd_verify_tree).  Equivalent to ssd_verify_tree with no drafts.
+ * masked positions by descending confidence, always one fewer than remain
+ * masked (see ssd_verify_tree).  Equivalent to ssd_verify_tree with no drafts.
  *   seqs      [n] host   sequence slots, distinct
  *   block_tok [n, cfg.block] host   tokens of the block (mask_id where masked)
  *   masked    [n] host   bit p set = position p is masked; bits >= block_len clear

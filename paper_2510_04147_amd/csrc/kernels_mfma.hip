@@ -817,19 +817,23 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
 // ------------------------------------------------------------------------
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-#define ATTN_WAVES 4   // waves per (node, head, query tile): wave w takes key tiles w, w+4, ...
+#define ATTN_WAVES 8   // waves per (node, head, query tile): wave w takes key tiles w, w+8, ...
 
 template <int DH>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* __restrict__ fw,
                                                                const bf16_t* __restrict__ q,
                                                                const bf16_t* __restrict__ kown,
-                                                               const bf16_t* __restrict__ vt,
+                                                               const bf16_t* __restrict__ vown,
                                                                const bf16_t* __restrict__ kcache,
                                                                const bf16_t* __restrict__ vcache,
                                                                bf16_t* __restrict__ out, int Hq, int Hkv, int layer,
                                                                int max_seqs, int seq_stride, int vt_rows, float scale) {
     constexpr int KST = DH / 16, DT = DH / 32;
-    __shared__ float mrg[ATTN_WAVES - 1][DT * 16 + 2][64];          // partial (O^T, max, sum) of waves 1..3
+    constexpr int NE = DT * 16;                                      // O^T values per lane
+    constexpr int EPW = NE / ATTN_WAVES;                             // of which each wave merges EPW
+    static_assert(EPW % 4 == 0, "the merge writes groups of four head channels");
+    __shared__ float mrg[ATTN_WAVES][NE + 2][64];                    // every wave's partial (O^T, max, sum)
+    __shared__ __attribute__((aligned(16))) bf16_t qs[32][DH + 8];   // the query tile, shared by the waves
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lm = lane & 31, lh = lane >> 5;
     const NodeDesc nd = fw->nodes[blockIdx.x];
@@ -841,15 +845,22 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     const bool qvalid = qrow_in < nd.blen;
     const int qrow = nd.row0 + (qvalid ? qrow_in : 0);
 
-    bf16x8 qf[KST];
-#pragma unroll
-    for (int ks = 0; ks < KST; ++ks) qf[ks] = *(const bf16x8*)(q + (size_t)qrow * nq + head * DH + ks * 16 + lh * 8);
+    // rows past the end of the block are read from row 0 and never written back
+    for (int idx = threadIdx.x; idx < 32 * (DH / 8); idx += ATTN_WAVES * 64) {
+        const int r = idx / (DH / 8), c8 = idx % (DH / 8);
+        const int rin = qt * 32 + r;
+        const int grow = nd.row0 + (rin < nd.blen ? rin : 0);
+        *(bf16x8*)&qs[r][c8 * 8] = *(const bf16x8*)(q + (size_t)grow * nq + head * DH + c8 * 8);
+    }
 
+    // keys and values of one KV head, fragment order: a tile of 32 positions is KST key pieces and
+    // 2*DT value pieces of 64 lanes x 8 elements each, fetched with one 16-byte load per lane
     const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)seq_stride * DH;
-    const bf16_t* kc = kcache + cbase;                              // [pos][DH]
-    const bf16_t* vc = vcache + cbase;                              // [DH][seq_stride]
-    const bf16_t* ko = kown + (size_t)nd.row0 * nkv + kvh * DH;     // [row][nkv]
-    const bf16_t* vo = vt + (size_t)kvh * DH * vt_rows + nd.vrow0;  // [DH][vt_rows]
+    const bf16_t* kc = kcache + cbase;
+    const bf16_t* vc = vcache + cbase;
+    const size_t obase = ((size_t)kvh * vt_rows + nd.vrow0) * DH;   // the node's rows start on a tile boundary
+    const bf16_t* ko = kown + obase;
+    const bf16_t* vo = vown + obase;
 
     floatx16 oacc[DT];
 #pragma unroll
@@ -859,41 +870,43 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     float m_run = -INFINITY, l_part = 0.f;
 
     const int pre_tiles = (nd.S + 31) >> 5, n_tiles = pre_tiles + ((nd.blen + 31) >> 5);
-    // key fragment loads of one tile (rows past the end are clamped to row 0 and masked later)
+    // positions past the end of the prefix or of the node hold stale memory: masked (keys) or zeroed (values)
     auto load_k = [&](bf16x8(&kf)[KST], int t) {
-        const bool own = t >= pre_tiles;
-        const int t0 = (own ? t - pre_tiles : t) * 32;
-        const int krow = t0 + lm < (own ? nd.blen : nd.S) ? t0 + lm : 0;
-        const bf16_t* kp = own ? ko + (size_t)krow * nkv : kc + (size_t)krow * DH;
+        const bf16_t* kp = (t >= pre_tiles ? ko + (size_t)(t - pre_tiles) * 32 * DH : kc + (size_t)t * 32 * DH) + lane * 8;
 #pragma unroll
-        for (int ks = 0; ks < KST; ++ks) kf[ks] = *(const bf16x8*)(kp + ks * 16 + lh * 8);
+        for (int ks = 0; ks < KST; ++ks) kf[ks] = *(const bf16x8*)(kp + ks * 512);
     };
-    bf16x8 kf[KST], kn[KST];
-    if (wave < n_tiles) load_k(kf, wave);
+    auto load_v = [&](bf16x8(&vf)[DT][2], int t) {
+        const bf16_t* vp = (t >= pre_tiles ? vo + (size_t)(t - pre_tiles) * 32 * DH : vc + (size_t)t * 32 * DH) + lane * 8;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) vf[dt][st] = *(const bf16x8*)(vp + (dt * 2 + st) * 512);
+    };
+    bf16x8 kf[KST], kn[KST], vf[DT][2], vn[DT][2];
+    if (wave < n_tiles) {
+        load_k(kf, wave);
+        load_v(vf, wave);
+    }
+    __syncthreads();                                                // the query tile is in LDS
     for (int t = wave; t < n_tiles; t += ATTN_WAVES) {
         const bool own = t >= pre_tiles;
         const int t0 = (own ? t - pre_tiles : t) * 32;              // first key of the tile, in its own index space
         const int n_valid = (own ? nd.blen : nd.S) - t0;            // keys of this tile that exist (may exceed 32)
-        // ---- values of this tile, position-contiguous: two 4-position runs per step
-        const bf16_t* vp = own ? vo : vc;
-        const size_t vstride = own ? (size_t)vt_rows : (size_t)seq_stride;
-        bf16x8 vf[DT][2];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const bf16_t* a = vp + (size_t)(dt * 32 + lm) * vstride + t0 + 16 * st + 4 * lh;
-                const bf16x4 lo = *(const bf16x4*)a, hi = *(const bf16x4*)(a + 8);
-                vf[dt][st] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-        // ---- keys of this wave's next tile, in flight while this tile is processed
-        if (t + ATTN_WAVES < n_tiles) load_k(kn, t + ATTN_WAVES);
+        // ---- this wave's next tile, in flight while this one is processed
+        if (t + ATTN_WAVES < n_tiles) {
+            load_k(kn, t + ATTN_WAVES);
+            load_v(vn, t + ATTN_WAVES);
+        }
         // ---- S^T = K Q^T
         floatx16 sacc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KST; ++ks) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], sacc, 0, 0, 0);
+        for (int ks = 0; ks < KST; ++ks) {
+            const bf16x8 qf = *(const bf16x8*)&qs[lm][ks * 16 + lh * 8];
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf, sacc, 0, 0, 0);
+        }
         // ---- online softmax over this lane's 16 keys (key = t0 + 8*(i/4) + 4*lh + i%4)
         float mx = -INFINITY;
 #pragma unroll
@@ -937,45 +950,52 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
         }
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks) kf[ks] = kn[ks];
-    }
-    // ---- merge the waves' partial results in wave order (fixed, independent of the forward's shape)
-    if (wave > 0) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mrg[wave - 1][dt * 16 + i][lane] = oacc[dt][i];
-        mrg[wave - 1][DT * 16][lane] = m_run;
-        mrg[wave - 1][DT * 16 + 1][lane] = l_part;
+            for (int st = 0; st < 2; ++st) vf[dt][st] = vn[dt][st];
     }
+    // ---- merge the waves' partial results: every wave publishes its partial, then wave w folds
+    // values [w*EPW, (w+1)*EPW) of all waves in wave order (fixed, independent of the forward's shape)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mrg[wave][dt * 16 + i][lane] = oacc[dt][i];
+    mrg[wave][NE][lane] = m_run;
+    mrg[wave][NE + 1][lane] = l_part;
     __syncthreads();
-    if (wave > 0) return;
+    float m_all = -INFINITY;
 #pragma unroll
-    for (int w = 1; w < ATTN_WAVES; ++w) {
-        const float m2 = mrg[w - 1][DT * 16][lane], l2 = mrg[w - 1][DT * 16 + 1][lane];
-        if (m2 == -INFINITY) continue;                               // that wave had no tile
-        const float m_new = fmaxf(m_run, m2);
-        const float c1 = expf(m_run - m_new), c2 = expf(m2 - m_new);
-        l_part = l_part * c1 + l2 * c2;
+    for (int w = 0; w < ATTN_WAVES; ++w) m_all = fmaxf(m_all, mrg[w][NE][lane]);
+    float cw[ATTN_WAVES], l = 0.f;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[dt][i] = oacc[dt][i] * c1 + mrg[w - 1][dt * 16 + i][lane] * c2;
-        m_run = m_new;
+    for (int w = 0; w < ATTN_WAVES; ++w) {
+        const float mw = mrg[w][NE][lane];
+        cw[w] = mw == -INFINITY ? 0.f : expf(mw - m_all);            // a wave without a tile counts for nothing
+        l += mrg[w][NE + 1][lane] * cw[w];
     }
-    const float l = l_part + __shfl_xor(l_part, 32, 64);
+    l += __shfl_xor(l, 32, 64);
     const float inv = 1.0f / l;
+    float o[EPW];
+#pragma unroll
+    for (int e = 0; e < EPW; ++e) {
+        float acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATTN_WAVES; ++w) acc += mrg[w][wave * EPW + e][lane] * cw[w];
+        o[e] = acc * inv;
+    }
     if (qvalid) {
         bf16_t* op = out + (size_t)qrow * nq + head * DH;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int g4 = 0; g4 < EPW / 4; ++g4) {
+            const int e = wave * EPW + g4 * 4;                       // first of four consecutive values
+            const int dt = e >> 4, g = (e & 15) >> 2;                // head channel = dt*32 + g*8 + lh*4 + j
+            uint16_t ob[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint16_t o[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) o[j] = f2bf_m(oacc[dt][g * 4 + j] * inv);
-                *(uint2*)(op + dt * 32 + g * 8 + lh * 4) =
-                    make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-            }
+            for (int j = 0; j < 4; ++j) ob[j] = f2bf_m(o[g4 * 4 + j]);
+            *(uint2*)(op + dt * 32 + g * 8 + lh * 4) =
+                make_uint2((uint32_t)ob[0] | ((uint32_t)ob[1] << 16), (uint32_t)ob[2] | ((uint32_t)ob[3] << 16));
+        }
     }
 }
 
@@ -984,7 +1004,7 @@ bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hi
     dim3 grid(n_nodes, d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
 #define SSD_ATTN_ARGS                                                                                                  \
-    c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.k, (const bf16_t*)c->b.vt, (const bf16_t*)c->b.kcache,      \
+    c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown, (const bf16_t*)c->b.kcache, \
         (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale
     if (d.dh == 128)
         k_attn_mfma<128><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);

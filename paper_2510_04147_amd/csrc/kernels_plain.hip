@@ -160,14 +160,14 @@ __global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float
 }
 
 // Rotary embedding (rotate-half pairing) of Q and K from the fp32 projection (the sum of its
-// split-K partial sums, in split order), conversion to the operand type, the transposed
-// (position-contiguous) copy of V, and the cache write for nodes that own finished tokens.
+// split-K partial sums, in split order), conversion to the operand type, the fragment-order copies
+// of the nodes' own keys and values, and the cache write for nodes that own finished tokens.
 // One work-group per (node, 32-row tile, head of Q, K or V): 32 rows x 8 column groups.
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, const float* __restrict__ part,
                                               int n_part, size_t part_stride, const float* __restrict__ cosT,
-                                              const float* __restrict__ sinT, T* __restrict__ q, T* __restrict__ k,
-                                              T* __restrict__ v, T* __restrict__ vt, int vt_rows,
+                                              const float* __restrict__ sinT, T* __restrict__ q,
+                                              T* __restrict__ kown, T* __restrict__ vown, int vt_rows,
                                               T* __restrict__ kcache, T* __restrict__ vcache, int Hq, int Hkv,
                                               int layer, int max_seqs, int seq_stride) {
     constexpr int HALF = DH / 2, PT = HALF / 8;          // q/k: values of each rotary half per thread
@@ -205,18 +205,30 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
             o2[j] = x2[j] * c + x1[j] * sn;
         }
         if (rvalid) {
-            T* dst = hh < Hq ? q + (size_t)row * nq + hh * DH : k + (size_t)row * nkv + (hh - Hq) * DH;
-#pragma unroll
-            for (int j = 0; j < PT; j += 4) {
-                st4(dst + i0 + j, o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
-                st4(dst + i0 + HALF + j, o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
-            }
-            if (hh >= Hq && nd.write_kv) {
-                T* kc = kcache + cbase + ((size_t)(hh - Hq) * seq_stride + pos) * DH;
+            if (hh < Hq) {
+                T* dst = q + (size_t)row * nq + hh * DH;
 #pragma unroll
                 for (int j = 0; j < PT; j += 4) {
-                    st4(kc + i0 + j, o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
-                    st4(kc + i0 + HALF + j, o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+                    st4(dst + i0 + j, o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
+                    st4(dst + i0 + HALF + j, o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+                }
+            } else {
+                // four consecutive channels starting at a multiple of four stay contiguous in fragment order
+                const int kvh = hh - Hq;
+                T* ko = kown + (size_t)kvh * vt_rows * DH;
+                T* kc = kcache + cbase + (size_t)kvh * seq_stride * DH;
+                const int prow = nd.vrow0 + r0 + r;
+#pragma unroll
+                for (int j = 0; j < PT; j += 4) {
+                    st4(ko + kfrag_off(prow, i0 + j, DH), o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
+                    st4(ko + kfrag_off(prow, i0 + HALF + j, DH), o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+                }
+                if (nd.write_kv) {
+#pragma unroll
+                    for (int j = 0; j < PT; j += 4) {
+                        st4(kc + kfrag_off(pos, i0 + j, DH), o1[j], o1[j + 1], o1[j + 2], o1[j + 3]);
+                        st4(kc + kfrag_off(pos, i0 + HALF + j, DH), o2[j], o2[j + 1], o2[j + 2], o2[j + 3]);
+                    }
                 }
             }
         }
@@ -227,22 +239,20 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
         load(nq + nkv + vh * DH + c0, x, VPT);
 #pragma unroll
         for (int j = 0; j < VPT; ++j) tile[r][c0 + j] = rvalid ? x[j] : 0.f;
-        if (rvalid) {
-            T* dst = v + (size_t)row * nkv + vh * DH + c0;
-#pragma unroll
-            for (int j = 0; j < VPT; j += 4) st4(dst + j, x[j], x[j + 1], x[j + 2], x[j + 3]);
-        }
         __syncthreads();
-        // transposed copy: thread -> (column, group of rows); a node's rows start 64-aligned
-        constexpr int TPC = 256 / DH, RPT = 32 / TPC;    // threads per column, rows per thread
+        // thread -> (channel, group of rows): four consecutive positions starting at a multiple of four
+        // stay contiguous in fragment order; a node's rows start 64-aligned, rows past its end get zeros
+        constexpr int TPC = 256 / DH, RPT = 32 / TPC;    // threads per channel, rows per thread
         const int col = tid / TPC, rg = (tid % TPC) * RPT;
-        T* vd = vt + (size_t)(vh * DH + col) * vt_rows + nd.vrow0 + r0 + rg;
+        T* vd = vown + (size_t)vh * vt_rows * DH;
 #pragma unroll
-        for (int j = 0; j < RPT; j += 4) st4(vd + j, tile[rg + j][col], tile[rg + j + 1][col], tile[rg + j + 2][col], tile[rg + j + 3][col]);
+        for (int j = 0; j < RPT; j += 4)
+            st4(vd + vfrag_off(nd.vrow0 + r0 + rg + j, col, DH), tile[rg + j][col], tile[rg + j + 1][col],
+                tile[rg + j + 2][col], tile[rg + j + 3][col]);
         if (nd.write_kv) {
-            T* vc = vcache + cbase + (size_t)(vh * DH + col) * seq_stride + nd.S + r0 + rg;
+            T* vc = vcache + cbase + (size_t)vh * seq_stride * DH;
             for (int j = 0; j < RPT; ++j)
-                if (r0 + rg + j < nd.blen) st_f(vc + j, tile[rg + j][col]);
+                if (r0 + rg + j < nd.blen) st_f(vc + vfrag_off(nd.S + r0 + rg + j, col, DH), tile[rg + j][col]);
         }
     }
 }
@@ -252,22 +262,23 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
 // key tiles of 64 in position order.
 template <typename T>
 __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__ fw, const int* __restrict__ row_node,
-                                                   const T* __restrict__ q, const T* __restrict__ k,
-                                                   const T* __restrict__ v, const T* __restrict__ kcache,
+                                                   const T* __restrict__ q, const T* __restrict__ kown,
+                                                   const T* __restrict__ vown, const T* __restrict__ kcache,
                                                    const T* __restrict__ vcache, T* __restrict__ out, int Hq,
-                                                   int Hkv, int dh, int layer, int max_seqs, int seq_stride) {
+                                                   int Hkv, int dh, int layer, int max_seqs, int seq_stride,
+                                                   int vt_rows) {
     const int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     const NodeDesc nd = fw->nodes[row_node[row]];
     const int kvh = head / (Hq / Hkv);
-    const int nq = Hq * dh, nkv = Hkv * dh;
+    const int nq = Hq * dh;
     __shared__ float qs[128];
     for (int i = lane; i < dh; i += 64) qs[i] = ld_f(q + (size_t)row * nq + head * dh + i);
     __syncthreads();
     const size_t cbase = ((((size_t)layer * max_seqs + nd.seq) * Hkv) + kvh) * (size_t)seq_stride * dh;
     const T* kc = kcache + cbase;
     const T* vc = vcache + cbase;
-    const T* kown = k + (size_t)nd.row0 * nkv + kvh * dh;
-    const T* vown = v + (size_t)nd.row0 * nkv + kvh * dh;
+    const T* ko = kown + (size_t)kvh * vt_rows * dh;
+    const T* vo = vown + (size_t)kvh * vt_rows * dh;
     const int n_keys = nd.S + nd.blen;
     const float scale = 1.0f / sqrtf((float)dh);
     float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
@@ -275,9 +286,11 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
         const int j = t0 + lane;
         float s = -INFINITY;
         if (j < n_keys) {
-            const T* kp = j < nd.S ? kc + (size_t)j * dh : kown + (size_t)(j - nd.S) * nkv;
+            const bool pre = j < nd.S;
+            const T* kp = pre ? kc : ko;
+            const int p = pre ? j : nd.vrow0 + j - nd.S;
             float acc = 0.f;
-            for (int i = 0; i < dh; ++i) acc += qs[i] * ld_f(kp + i);
+            for (int i = 0; i < dh; ++i) acc += qs[i] * ld_f(kp + kfrag_off(p, i, dh));
             s = acc * scale;
         }
         const float m_new = fmaxf(m, wave_max(s));
@@ -290,12 +303,11 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
         for (int jj = 0; jj < cnt; ++jj) {
             const float pj = __shfl(p, jj, 64);
             const int jk = t0 + jj;
-            // cached values are stored position-contiguous: element (pos, i) at [i * seq_stride + pos]
             const bool pre = jk < nd.S;
-            const T* vp = pre ? vc + jk : vown + (size_t)(jk - nd.S) * nkv;
-            const size_t es = pre ? (size_t)seq_stride : 1;
-            o0 += pj * ld_f(vp + lane * es);
-            if (dh > 64) o1 += pj * ld_f(vp + (lane + 64) * es);
+            const T* vp = pre ? vc : vo;
+            const int pp = pre ? jk : nd.vrow0 + jk - nd.S;
+            o0 += pj * ld_f(vp + vfrag_off(pp, lane, dh));
+            if (dh > 64) o1 += pj * ld_f(vp + vfrag_off(pp, lane + 64, dh));
         }
         m = m_new;
     }
@@ -416,8 +428,9 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const T* __restrict__ X, con
 }
 
 // Merge the per-tile (max, arg, sumexp) triples of a row in a fixed order:
-// each lane folds tiles lane, lane+64, ... in ascending order, then the 64
-// lanes are folded by a butterfly.  Ties keep the lowest token id.
+// each thread folds tiles tid, tid+256, ... in ascending order, then the 64
+// lanes of a wave are folded by a butterfly and the four waves in order.
+// Ties keep the lowest token id.
 __device__ __forceinline__ void lm_fold(float& m, int& a, float& s, float om, int oa, float os) {
     if (os == 0.f) return;                 // empty partner
     if (s == 0.f) { m = om; a = oa; s = os; return; }
@@ -427,13 +440,17 @@ __device__ __forceinline__ void lm_fold(float& m, int& a, float& s, float om, in
     m = nm;
 }
 
-__global__ __launch_bounds__(64) void k_lm_merge(const float* __restrict__ part, int n_tiles,
-                                                 float* __restrict__ row_max, int* __restrict__ row_arg,
-                                                 float* __restrict__ row_conf, int V, int mask_id) {
-    const int row = blockIdx.x, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void k_lm_merge(const float* __restrict__ part, int n_tiles,
+                                                  float* __restrict__ row_max, int* __restrict__ row_arg,
+                                                  float* __restrict__ row_conf, int V, int mask_id) {
+    // One work-group per row.  The fold order (tile t goes to thread t mod 256, then a butterfly
+    // inside each wave, then waves 0..3 in order) depends on the tile count alone.
+    __shared__ float sm[4], ss[4];
+    __shared__ int sa[4];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float m = -INFINITY, s = 0.f;
     int a = 0x7fffffff;
-    for (int t = lane; t < n_tiles; t += 64) {
+    for (int t = tid; t < n_tiles; t += 256) {
         const float* p = part + ((size_t)row * n_tiles + t) * 3;
         lm_fold(m, a, s, p[0], __float_as_int(p[1]), p[2]);
     }
@@ -451,7 +468,10 @@ __global__ __launch_bounds__(64) void k_lm_merge(const float* __restrict__ part,
             lm_fold(m, a, s, om, oa, os);
         }
     }
-    if (lane == 0) {
+    if (lane == 0) { sm[wave] = m; sa[wave] = a; ss[wave] = s; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w) lm_fold(m, a, s, sm[w], sa[w], ss[w]);
         // Non-finite logits (NaN weights) leave no arg-max: fall back to the lowest valid id and
         // confidence 0 so that every later step stays well defined and in bounds.
         if ((unsigned)a >= (unsigned)V) a = mask_id == 0 ? 1 : 0;
@@ -587,7 +607,7 @@ void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_p
     const size_t ps = (size_t)d.max_rows * c->part_cols;
     dim3 grid(n_nodes, (max_blen + 31) / 32, d.Hq + 2 * d.Hkv);
 #define SSD_ROPE_ARGS(T)                                                                                           \
-    c->b.fwd, c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin, (T*)c->b.q, (T*)c->b.k, (T*)c->b.v, (T*)c->b.vt, \
+    c->b.fwd, c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin, (T*)c->b.q, (T*)c->b.kown, (T*)c->b.vown,        \
         d.vt_rows(), (T*)c->b.kcache, (T*)c->b.vcache, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride()
     if (d.dtype == SSD_F32) {
         if (d.dh == 128) k_rope<float, 128><<<grid, 256, 0, st>>>(SSD_ROPE_ARGS(float));
@@ -603,16 +623,17 @@ void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st) {
     const Dims& d = c->dm;
     dim3 grid(M, d.Hq);
     if (d.dtype == SSD_F32)
-        k_attn_plain<float><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const float*)c->b.q, (const float*)c->b.k,
-                                                 (const float*)c->b.v, (const float*)c->b.kcache,
-                                                 (const float*)c->b.vcache, (float*)c->b.attn, d.Hq, d.Hkv, d.dh,
-                                                 layer, d.max_seqs, d.seq_stride());
+        k_attn_plain<float><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const float*)c->b.q,
+                                                 (const float*)c->b.kown, (const float*)c->b.vown,
+                                                 (const float*)c->b.kcache, (const float*)c->b.vcache,
+                                                 (float*)c->b.attn, d.Hq, d.Hkv, d.dh, layer, d.max_seqs,
+                                                 d.seq_stride(), d.vt_rows());
     else
         k_attn_plain<bf16_t><<<grid, 64, 0, st>>>(c->b.fwd, c->b.row_node, (const bf16_t*)c->b.q,
-                                                  (const bf16_t*)c->b.k, (const bf16_t*)c->b.v,
+                                                  (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown,
                                                   (const bf16_t*)c->b.kcache, (const bf16_t*)c->b.vcache,
                                                   (bf16_t*)c->b.attn, d.Hq, d.Hkv, d.dh, layer, d.max_seqs,
-                                                  d.seq_stride());
+                                                  d.seq_stride(), d.vt_rows());
 }
 
 template <typename T>
@@ -638,7 +659,7 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
 int lm_tiles_plain(int V) { return (V + PBN - 1) / PBN; }
 
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
-    k_lm_merge<<<M, 64, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf, c->dm.V,
+    k_lm_merge<<<M, 256, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf, c->dm.V,
                                  c->dm.mask_id);
 }
 

@@ -106,9 +106,8 @@ static size_t carve(const Dims& d, char* base, Buffers* b) {
     t.h = (float*)take(R * d.d * 4);
     t.xn = take(R * d.d * e);
     t.q = take(R * d.nq() * e);
-    t.k = take(R * d.nkv() * e);
-    t.v = take(R * d.nkv() * e);
-    t.vt = take((size_t)d.nkv() * d.vt_rows() * e);
+    t.kown = take((size_t)d.nkv() * d.vt_rows() * e);
+    t.vown = take((size_t)d.nkv() * d.vt_rows() * e);
     t.attn = take(R * d.nq() * e);
     t.act = take(R * d.F * e);
     const size_t pc = d.nqkv() > d.d ? d.nqkv() : d.d;

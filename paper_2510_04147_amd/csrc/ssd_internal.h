@@ -32,7 +32,7 @@ struct NodeDesc {
     int seq, row0, blen, S;
     int group, j;   // j = index of the node inside its group = number of drafts written in
     int write_kv;
-    int vrow0;      // 64-aligned start of the node's rows in the transposed own-value buffer
+    int vrow0;      // 64-aligned start of the node's rows in the own-key / own-value buffers
 };
 
 struct FwdHeader {
@@ -76,18 +76,34 @@ struct Dims {
     size_t esz() const { return dtype == SSD_F32 ? 4 : 2; }
     // positions allocated per cache slot: whole 64-position tiles, so tile loads stay in bounds
     int seq_stride() const { return (max_seq_len + 63) & ~63; }
-    // rows of the transposed own-value buffer: every node starts on a 64-row boundary
+    // rows of the own-key / own-value buffers: every node starts on a 64-row boundary
     int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * SSD_MAX_NODES; }
 };
+
+// Keys and values, cached or of the forward's own rows, are stored per KV head in the order the
+// attention kernel's matrix instructions consume them, so that a wave fetches each operand
+// fragment as one contiguous 64 x 8 element piece.  Position p, head channel c, head size dh:
+//   keys:   [p/32][c/16][lane = (c/8 % 2)*32 + p%32][c%8]
+//           (fragment ks = c/16 of S^T = K Q^T: lane (p%32, half) holds 8 consecutive channels);
+//   values: [p/32][c/32][p/16 % 2][lane = (p/4 % 2)*32 + c%32][(p/8 % 2)*4 + p%4]
+//           (fragment of O^T = V^T P^T: lane (c%32, half) holds the 8 keys whose probabilities
+//           the same lane half holds after the S^T product).
+// A head's region of n positions (n a multiple of 32) holds n*dh elements in either order.
+__host__ __device__ inline size_t kfrag_off(int p, int c, int dh) {
+    return ((((size_t)(p >> 5) * (dh >> 4) + (c >> 4)) * 64 + ((c >> 3) & 1) * 32 + (p & 31)) << 3) + (c & 7);
+}
+__host__ __device__ inline size_t vfrag_off(int p, int c, int dh) {
+    return (((((size_t)(p >> 5) * (dh >> 5) + (c >> 5)) * 2 + ((p >> 4) & 1)) * 64 + ((p >> 2) & 1) * 32 + (c & 31)) << 3) +
+           ((p >> 3) & 1) * 4 + (p & 3);
+}
 
 // Workspace carve-up (all device pointers into the caller's workspace).
 struct Buffers {
     float* h;            // [max_rows, d] residual stream, fp32
     void* xn;            // [max_rows, d] normed rows, T
     void* q;             // [max_rows, nq] T, after rotary
-    void* k;             // [max_rows, nkv] T, after rotary (the node's own keys)
-    void* v;             // [max_rows, nkv] T
-    void* vt;            // [Hkv][dh][vt_rows] T: the same values, position-contiguous (MFMA operand order)
+    void* kown;          // [Hkv][vt_rows * dh] T: the nodes' own keys after rotary, fragment order (kfrag_off)
+    void* vown;          // [Hkv][vt_rows * dh] T: the nodes' own values, fragment order (vfrag_off)
     void* attn;          // [max_rows, nq] T
     void* act;           // [max_rows, F] T
     float* part;         // [SSD_MAX_SPLIT, max_rows, max(d, nqkv)] fp32 split-K partial sums of the
@@ -101,8 +117,8 @@ struct Buffers {
     int* row_pos;        // [max_rows]
     int* row_node;       // [max_rows]
     int* raw_tok;        // [max_rows]
-    void* kcache;        // [L][max_seqs][Hkv][seq_stride][dh] T, keys after rotary embedding
-    void* vcache;        // [L][max_seqs][Hkv][dh][seq_stride] T, position-contiguous
+    void* kcache;        // [L][max_seqs][Hkv][seq_stride * dh] T, keys after rotary, fragment order
+    void* vcache;        // [L][max_seqs][Hkv][seq_stride * dh] T, values, fragment order
     float* rope_cos;     // [max_seq_len, dh/2]
     float* rope_sin;
     FwdHeader* fwd;      // device copy of the descriptor

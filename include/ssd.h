@@ -68,6 +68,7 @@ typedef struct ssd_ctx ssd_ctx;   /* opaque */
 
 typedef struct {
     int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, mask_id;
+                               /* d_model <= 8192, a multiple of 8; head_dim 64 or 128           */
     int dtype;                 /* SSD_F32 or SSD_BF16: type of weights, KV cache, GEMM operands */
     float rope_theta, rms_eps;
     int max_seqs;              /* sequence slots in the KV cache                               */
@@ -124,8 +125,8 @@ size_t ssd_workspace_bytes(const ssd_config* cfg);
  * 256-byte aligned; `hip_stream` is a hipStream_t (NULL = the default stream).
  * The weights must be completely written before the call: bf16 weights are
  * repacked into the workspace by kernels on `hip_stream`.
- * Errors: SSD_EINVAL (null / inconsistent config), SSD_ERANGE (block, draft or
- * head_dim beyond the supported limits), SSD_ENOMEM, SSD_EHIP. */
+ * Errors: SSD_EINVAL (null / inconsistent config), SSD_ERANGE (block, draft,
+ * d_model or head_dim beyond the supported limits), SSD_ENOMEM, SSD_EHIP. */
 int ssd_create(const ssd_config* cfg, const ssd_weights* weights, void* workspace,
                size_t workspace_bytes, void* hip_stream, ssd_ctx** out);
 int ssd_destroy(ssd_ctx* ctx);

@@ -836,22 +836,28 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     __shared__ __attribute__((aligned(16))) bf16_t qs[32][DH + 8];   // the query tile, shared by the waves
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lm = lane & 31, lh = lane >> 5;
-    const NodeDesc nd = fw->nodes[blockIdx.x];
-    const int head = blockIdx.y, kvh = head / (Hq / Hkv);
-    const int qt = blockIdx.z;
+    // Work-groups go to the 8 XCDs round-robin by their linear id, and every XCD has an L2 of its
+    // own: all (node, query head) pairs that read one KV head are placed on the same XCD, so the
+    // prefix is fetched from HBM once and the other nodes hit in L2.
+    const int n_nodes = gridDim.x / Hq, G = Hq / Hkv;
+    int node, head;
+    if (Hkv % 8 == 0) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        node = slot % n_nodes;
+        const int rest = slot / n_nodes;
+        head = ((rest / G) * 8 + xcd) * G + rest % G;
+    } else {
+        node = blockIdx.x % n_nodes;
+        head = blockIdx.x / n_nodes;
+    }
+    const NodeDesc nd = fw->nodes[node];
+    const int kvh = head / G;
+    const int qt = blockIdx.y;
     if (qt * 32 >= nd.blen) return;                                  // uniform over the work-group
-    const int nq = Hq * DH, nkv = Hkv * DH;
+    const int nq = Hq * DH;
     const int qrow_in = qt * 32 + lm;
     const bool qvalid = qrow_in < nd.blen;
     const int qrow = nd.row0 + (qvalid ? qrow_in : 0);
-
-    // rows past the end of the block are read from row 0 and never written back
-    for (int idx = threadIdx.x; idx < 32 * (DH / 8); idx += ATTN_WAVES * 64) {
-        const int r = idx / (DH / 8), c8 = idx % (DH / 8);
-        const int rin = qt * 32 + r;
-        const int grow = nd.row0 + (rin < nd.blen ? rin : 0);
-        *(bf16x8*)&qs[r][c8 * 8] = *(const bf16x8*)(q + (size_t)grow * nq + head * DH + c8 * 8);
-    }
 
     // keys and values of one KV head, fragment order: a tile of 32 positions is KST key pieces and
     // 2*DT value pieces of 64 lanes x 8 elements each, fetched with one 16-byte load per lane
@@ -887,6 +893,14 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     if (wave < n_tiles) {
         load_k(kf, wave);
         load_v(vf, wave);
+    }
+    // the query tile, after the first key/value loads are on their way; rows past the end of the
+    // block are read from row 0 and never written back
+    for (int idx = threadIdx.x; idx < 32 * (DH / 8); idx += ATTN_WAVES * 64) {
+        const int r = idx / (DH / 8), c8 = idx % (DH / 8);
+        const int rin = qt * 32 + r;
+        const int grow = nd.row0 + (rin < nd.blen ? rin : 0);
+        *(bf16x8*)&qs[r][c8 * 8] = *(const bf16x8*)(q + (size_t)grow * nq + head * DH + c8 * 8);
     }
     __syncthreads();                                                // the query tile is in LDS
     for (int t = wave; t < n_tiles; t += ATTN_WAVES) {
@@ -1001,7 +1015,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
 
 bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hipStream_t st) {
     const Dims& d = c->dm;
-    dim3 grid(n_nodes, d.Hq, (max_blen + 31) / 32);
+    dim3 grid(n_nodes * d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
 #define SSD_ATTN_ARGS                                                                                                  \
     c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown, (const bf16_t*)c->b.kcache, \

@@ -86,9 +86,11 @@ __global__ void k_embed(const T* __restrict__ embed, const int* __restrict__ row
 }
 
 // a2/a6/a9: h += sum of split-K partial sums (fixed order s = 0, 1, ...), then RMSNorm.
-// One work-group per row; every thread owns up to NORM_J float4 groups of the row, all
-// partial-sum loads are issued before the first add.
-#define NORM_J 8   // 256 threads x 8 float4 = rows up to 8192 wide
+// One work-group of NORM_T threads per row; every thread owns up to NORM_J float4 groups of the
+// row and issues all partial-sum loads of a group before the first add, so a 4096-wide row has
+// its whole input (the row and every partial sum) in flight at once.
+#define NORM_T 1024
+#define NORM_J 2   // 1024 threads x 2 float4 = rows up to 8192 wide
 __device__ __forceinline__ void st4(float* p, float a, float b, float c, float d) { *(float4*)p = make_float4(a, b, c, d); }
 __device__ __forceinline__ void st4(bf16_t* p, float a, float b, float c, float d) {
     *(uint2*)p = make_uint2((uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16), (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16));
@@ -102,7 +104,7 @@ __device__ __forceinline__ void norm_row(float* hr, const float* pr, size_t part
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < NORM_J; ++j) {
-        const int i4 = threadIdx.x + j * 256;
+        const int i4 = threadIdx.x + j * NORM_T;
         if (i4 < n4) {
             v[j] = ((const float4*)hr)[i4];
             float4 pv[NP > 0 ? NP : 1];
@@ -116,15 +118,17 @@ __device__ __forceinline__ void norm_row(float* hr, const float* pr, size_t part
             ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
         }
     }
-    __shared__ float red[4];
+    __shared__ float red[NORM_T / 64];
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NORM_T / 64; ++w) tot += red[w];
     const float r = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
     for (int j = 0; j < NORM_J; ++j) {
-        const int i4 = threadIdx.x + j * 256;
+        const int i4 = threadIdx.x + j * NORM_T;
         if (i4 < n4) {
             const float4 g = ((const float4*)gain)[i4];
             st4(xr + 4 * i4, v[j].x * r * g.x, v[j].y * r * g.y, v[j].z * r * g.z, v[j].w * r * g.w);
@@ -133,7 +137,7 @@ __device__ __forceinline__ void norm_row(float* hr, const float* pr, size_t part
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float* __restrict__ part, int n_part,
+__global__ __launch_bounds__(NORM_T) void k_norm(float* __restrict__ h, const float* __restrict__ part, int n_part,
                                               size_t part_stride, const float* __restrict__ gain,
                                               T* __restrict__ xn, int d, float eps) {
     const int row = blockIdx.x;
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(256) void k_norm(float* __restrict__ h, const float
         case 8: norm_row<T, 8>(hr, pr, part_stride, gain, xr, d, eps); break;
         default: {
             // any other split count: fold the partial sums into h first, in order
-            for (int i = threadIdx.x; i < d; i += 256) {
+            for (int i = threadIdx.x; i < d; i += NORM_T) {
                 float v = hr[i];
                 for (int s = 0; s < n_part; ++s) v += pr[s * part_stride + i];
                 hr[i] = v;
@@ -596,9 +600,9 @@ void launch_embed(const ssd_ctx* c, int M, hipStream_t st) {
 void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st) {
     const size_t stride = (size_t)c->dm.max_rows * c->part_cols;
     if (c->dm.dtype == SSD_F32)
-        k_norm<float><<<M, 256, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (float*)c->b.xn, c->dm.d, c->dm.eps);
+        k_norm<float><<<M, NORM_T, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (float*)c->b.xn, c->dm.d, c->dm.eps);
     else
-        k_norm<bf16_t><<<M, 256, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (bf16_t*)c->b.xn, c->dm.d,
+        k_norm<bf16_t><<<M, NORM_T, 0, st>>>(c->b.h, c->b.part, n_part, stride, gain, (bf16_t*)c->b.xn, c->dm.d,
                                           c->dm.eps);
 }
 

@@ -60,6 +60,7 @@ static int check_config(const ssd_config* cfg, std::string* why) {
     if (cfg->n_q_heads % cfg->n_kv_heads) return bad(SSD_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return bad(SSD_ERANGE, "head_dim must be 64 or 128");
     if (cfg->d_model % 8 || cfg->d_ffn % 8) return bad(SSD_EINVAL, "d_model and d_ffn must be multiples of 8");
+    if (cfg->d_model > 8192) return bad(SSD_ERANGE, "d_model exceeds 8192");
     if (cfg->mask_id < 0 || cfg->mask_id >= cfg->vocab) return bad(SSD_EINVAL, "mask_id outside the vocabulary");
     if (cfg->block > SSD_MAX_BLOCK) return bad(SSD_ERANGE, "block exceeds SSD_MAX_BLOCK");
     if (cfg->max_draft > SSD_MAX_DRAFT) return bad(SSD_ERANGE, "max_draft exceeds SSD_MAX_DRAFT");

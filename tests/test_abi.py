@@ -50,7 +50,7 @@ def test_config_validation_needs_no_gpu(lib):
     good = binding.make_config(cfg, 1, 256, 32, 4)
     assert lib.ssd_workspace_bytes(ctypes.byref(good)) > 0
     for field, value in [("block", 65), ("max_draft", 16), ("head_dim", 80), ("n_kv_heads", 3), ("dtype", 7),
-                         ("mask_id", 5000), ("max_seqs", 17), ("d_model", 250)]:
+                         ("mask_id", 5000), ("max_seqs", 17), ("d_model", 250), ("d_model", 8200)]:
         bad = binding.make_config(cfg, 1, 256, 32, 4)
         setattr(bad, field, value)
         bad.max_rows = 1 << 20

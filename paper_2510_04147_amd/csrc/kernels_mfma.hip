@@ -92,8 +92,8 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s
 // ------------------------------------------------------------------------
 template <int WN, int WK, int R, int MT, int EPI, int NCH, int DBG = 0, int DW = 4, int PX = 4, int KSTEPS = 2>
 __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, const uint4* Wp, void* outv, int M, int N,
-                                                           int K, int k_len, size_t split_stride, int up_tile_off,
-                                                           int mask_id, int n_tiles_out) {
+                                                           int K, int ldx, int k_len, size_t split_stride,
+                                                           int up_tile_off, int mask_id, int n_tiles_out) {
     constexpr int T = WN * WK * 64, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
     constexpr int NST = 3;                              // LDS stages
     static_assert(DW >= 2 && DW <= 6 && PX >= 3 && PX <= 4, "ring depths");
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         const int seg = tid + i * T;
         const int m = seg / (KC / 8), sg = seg - m * (KC / 8);
         xok[i] = seg < XSEG && m0 + m < M;
-        xsrc[i] = X + (size_t)(xok[i] ? m0 + m : 0) * K + kbeg + sg * 8;
+        xsrc[i] = X + (size_t)(xok[i] ? m0 + m : 0) * ldx + kbeg + sg * 8;
         xdst[i] = seg < XSEG ? m * LDW + sg * 8 : SPARE + tid * 8;
     }
 
@@ -271,6 +271,104 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sum += acc[r][mt][i];
         if (sum == 1.2345f) *(float*)outv = sum;
+        return;
+    }
+
+    // ---- epilogues.  Lane (lm, lh) holds, per tile, rows n = 8*(i/4) + 4*lh + i%4 of column m = lm;
+    // g = i/4 selects a group of four consecutive n.
+    if constexpr (WK == 2 && R == 1 && EPI == EPI_F32) {
+        // The two k-slice waves of an n-tile share the output: wave wk keeps groups 2wk, 2wk+1 and
+        // hands the other two to its partner through LDS, so both waves add and store (k-slice 0
+        // plus k-slice 1, the order of the sequential reduction).
+        float4* ex = (float4*)smem_u4;                  // [WN][sender wk][MT][2][64]
+        static_for<0, 2>([&](auto iw) {
+            constexpr int w = decltype(iw)::value;
+            if (wk == w) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int gq = 0; gq < 2; ++gq) {
+                        constexpr int gbase = (1 - w) * 2;
+                        const int g = gbase + gq;
+                        ex[(((wn * 2 + w) * MT + mt) * 2 + gq) * 64 + lane] =
+                            make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
+                    }
+            }
+        });
+        __syncthreads();
+        float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
+        static_for<0, 2>([&](auto iw) {
+            constexpr int w = decltype(iw)::value;
+            if (wk == w && nt_ok[0]) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int m = m0 + mt * 32 + lm;
+#pragma unroll
+                    for (int gq = 0; gq < 2; ++gq) {
+                        constexpr int gbase = w * 2;
+                        const int g = gbase + gq;
+                        const float4 o = ex[(((wn * 2 + (1 - w)) * MT + mt) * 2 + gq) * 64 + lane];
+                        const int n = nt[0] * 32 + g * 8 + lh * 4;
+                        if (m < M)
+                            *(float4*)(out + (size_t)m * N + n) =
+                                make_float4(acc[0][mt][g * 4] + o.x, acc[0][mt][g * 4 + 1] + o.y,
+                                            acc[0][mt][g * 4 + 2] + o.z, acc[0][mt][g * 4 + 3] + o.w);
+                    }
+                }
+            }
+        });
+        return;
+    }
+    if constexpr (WK == 2 && R == 1 && EPI == EPI_SWIGLU) {
+        // The four waves of a channel tile (gate / up x two k-slices) share the output: wave
+        // q = (up ? 1 : 0) + 2 wk finishes group g = q of every row tile and receives the other three
+        // waves' values of that group through LDS.  gate = k-slice 0 + k-slice 1, likewise up.
+        float4* ex = (float4*)smem_u4;                  // [WN/2][receiver][3 senders][MT][64]
+        const int pr = wn >> 1, q = (wn & 1) + 2 * wk;
+        static_for<0, 4>([&](auto iq) {
+            constexpr int me = decltype(iq)::value;
+            if (q == me) {
+                static_for<0, 4>([&](auto ig) {
+                    constexpr int g = decltype(ig)::value;          // receiver
+                    if constexpr (g != me) {
+                        constexpr int slot = me < g ? me : me - 1;
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            ex[(((pr * 4 + g) * 3 + slot) * MT + mt) * 64 + lane] =
+                                make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
+                    }
+                });
+            }
+        });
+        __syncthreads();
+        bf16_t* out = (bf16_t*)outv;
+        const int ch = blockIdx.x * (WN / 2) + pr;
+        static_for<0, 4>([&](auto iq) {
+            constexpr int me = decltype(iq)::value;
+            if (q == me && ch < up_tile_off) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    float4 v[4];                                    // by sender: gate k0, up k0, gate k1, up k1
+                    static_for<0, 4>([&](auto is) {
+                        constexpr int sd = decltype(is)::value;
+                        if constexpr (sd == me)
+                            v[sd] = make_float4(acc[0][mt][me * 4], acc[0][mt][me * 4 + 1], acc[0][mt][me * 4 + 2], acc[0][mt][me * 4 + 3]);
+                        else
+                            v[sd] = ex[(((pr * 4 + me) * 3 + (sd < me ? sd : sd - 1)) * MT + mt) * 64 + lane];
+                    });
+                    const float gv[4] = {v[0].x + v[2].x, v[0].y + v[2].y, v[0].z + v[2].z, v[0].w + v[2].w};
+                    const float uv[4] = {v[1].x + v[3].x, v[1].y + v[3].y, v[1].z + v[3].z, v[1].w + v[3].w};
+                    uint16_t o[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) o[j] = f2bf_m(gv[j] / (1.0f + expf(-gv[j])) * uv[j]);
+                    const int m = m0 + mt * 32 + lm;
+                    const int f = ch * 32 + me * 8 + lh * 4;
+                    if (m < M)
+                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
+                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
+                }
+            }
+        });
         return;
     }
 
@@ -418,271 +516,6 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 }
 
 // ------------------------------------------------------------------------
-// GEMM, producer/consumer form.  Loads complete in issue order within a wave, so a wave that
-// both keeps a deep queue of HBM weight loads in flight and has to wait for an activation load
-// every chunk ends up waiting for its weight queue.  Here the two streams live in different
-// waves: WN*WK consumer waves stream weights into registers and run the MFMAs, NP producer
-// waves do nothing but move activation chunks global -> registers -> LDS.  One barrier per
-// chunk joins them.  Everything else (tiling, rotation, epilogues) is as in k_gemm_mfma.
-// ------------------------------------------------------------------------
-template <int WN, int WK, int NP, int MT, int EPI, int NCH, int DBG = 0, int DW = 3, int PX = 2, int KSTEPS = 2>
-__global__ __launch_bounds__((WN * WK + NP) * 64) void k_gemm_pc(const bf16_t* X, const uint4* Wp, void* outv, int M,
-                                                                 int N, int K, int k_len, size_t split_stride,
-                                                                 int up_tile_off, int mask_id, int n_tiles_out) {
-    constexpr int NC = WN * WK, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
-    constexpr int TP = NP * 64;
-    constexpr int XSEG = ROWS * (KC / 8), XPT = (XSEG + TP - 1) / TP, SPARE = 2 * ROWS * LDW;
-    static_assert(DW >= 2 && DW <= 4 && PX >= 1 && PX <= 3, "ring depths");
-    extern __shared__ uint4 smem_u4[];
-    bf16_t* xs = (bf16_t*)smem_u4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.y * ROWS;
-    const int kbeg = blockIdx.z * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
-    const int rot = (int)((blockIdx.x * 5u + blockIdx.z * 3u) % (unsigned)nchunks);
-    auto chunk_at = [&](int c) {
-        c = c < nchunks - 1 ? c : nchunks - 1;
-        c += rot;
-        return c >= nchunks ? c - nchunks : c;
-    };
-    if (wave >= NC) {
-        // ------------------------------------------------ producer: activations only
-        const int pt = tid - NC * 64;
-        const bf16_t* xsrc[XPT];
-        int xdst[XPT];
-        bool xok[XPT];
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            const int seg = pt + i * TP;
-            const int m = seg / (KC / 8), sg = seg - m * (KC / 8);
-            xok[i] = seg < XSEG && m0 + m < M;
-            xsrc[i] = X + (size_t)(xok[i] ? m0 + m : 0) * K + kbeg + sg * 8;
-            xdst[i] = seg < XSEG ? m * LDW + sg * 8 : SPARE + pt * 8;
-        }
-        uint4 x0[XPT], x1[XPT], x2[XPT];
-#define SSD_XSLOT(i) ((i) % PX == 0 ? x0 : (i) % PX == 1 ? x1 : x2)
-        auto issue_x = [&](uint4* dst, int c) {
-            const size_t off = (size_t)chunk_at(c) * KC;
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) dst[i] = *(const uint4*)(xsrc[i] + off);
-        };
-        auto stage_x = [&](const uint4* src, int buf) {
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) {
-                uint4 v = src[i];
-                if (!xok[i]) v = make_uint4(0, 0, 0, 0);
-                const int off = xdst[i] < SPARE ? buf * ROWS * LDW + xdst[i] : xdst[i];
-                *(uint4*)(xs + off) = v;
-            }
-        };
-        static_for<0, PX>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_x(SSD_XSLOT(u), u); });
-        stage_x(x0, 0);
-        __syncthreads();
-        if constexpr (NCH > 0) {
-            static_for<0, NCH>([&](auto ic) {
-                constexpr int c = decltype(ic)::value;
-                if constexpr (c + PX < NCH) issue_x(SSD_XSLOT(c + PX), c + PX);
-                if constexpr (c + 1 < NCH) stage_x(SSD_XSLOT(c + 1), (c + 1) & 1);
-                __syncthreads();
-            });
-        } else {
-            constexpr int UN = 2 * PX;
-            for (int c0 = 0; c0 < nchunks; c0 += UN)
-                static_for<0, UN>([&](auto ic) {
-                    constexpr int u = decltype(ic)::value;
-                    if (c0 + u < nchunks) {
-                        issue_x(SSD_XSLOT(u + PX), c0 + u + PX);
-                        stage_x(SSD_XSLOT(u + 1), (u + 1) & 1);
-                        __syncthreads();
-                    }
-                });
-        }
-#undef SSD_XSLOT
-        if (!(DBG & 4)) {
-            if (WK > 1) __syncthreads();
-            if (EPI == EPI_SWIGLU) { if (WK > 1) __syncthreads(); __syncthreads(); }
-        }
-        return;
-    }
-    // ---------------------------------------------------- consumers: weights + MFMA
-    const int wn = wave % WN, wk = wave / WN;
-    const int lm = lane & 31, lh = lane >> 5;
-    const int KS = K >> 4, NT = N >> 5;
-    int nt0;
-    bool nt_ok0;
-    if (EPI == EPI_SWIGLU) {
-        const int ch = blockIdx.x * (WN / 2) + (wn >> 1);
-        nt_ok0 = ch < up_tile_off;
-        nt0 = (nt_ok0 ? ch : up_tile_off - 1) + ((wn & 1) ? up_tile_off : 0);
-    } else {
-        nt0 = blockIdx.x * WN + wn;
-        nt_ok0 = nt0 < NT;
-        if (!nt_ok0) nt0 = NT - 1;
-    }
-    const uint4* wbase = Wp + ((size_t)nt0 * KS + (kbeg >> 4) + wk * KSTEPS) * 64 + lane;
-    floatx16 acc[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[mt][i] = 0.f;
-    uint4 w0[KSTEPS], w1[KSTEPS], w2[KSTEPS], w3[KSTEPS];
-#define SSD_WSLOT(i) ((i) % DW == 0 ? w0 : (i) % DW == 1 ? w1 : (i) % DW == 2 ? w2 : w3)
-    auto issue_w = [&](uint4* dst, int c) {
-        const uint4* p = wbase + (size_t)chunk_at(c) * (KC / 16) * 64;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) dst[ks] = p[ks * 64];
-    };
-    auto multiply = [&](const uint4* w, int buf) {
-        const bf16_t* xb = xs + (size_t)buf * ROWS * LDW + wk * KW + lh * 8;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            bf16x8 xf[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) xf[mt] = *(const bf16x8*)(xb + (size_t)(mt * 32 + lm) * LDW + ks * 16);
-            __builtin_amdgcn_sched_barrier(0);
-            const uint4 wv = w[ks];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-                acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&wv, xf[mt], acc[mt], 0, 0, 0);
-        }
-    };
-    static_for<0, DW - 1>([&](auto ic) { constexpr int u = decltype(ic)::value; issue_w(SSD_WSLOT(u), u); });
-    __syncthreads();
-    if constexpr (NCH > 0) {
-        static_for<0, NCH>([&](auto ic) {
-            constexpr int c = decltype(ic)::value;
-            if constexpr (c + DW - 1 < NCH) issue_w(SSD_WSLOT(c + DW - 1), c + DW - 1);
-            multiply(SSD_WSLOT(c), c & 1);
-            __syncthreads();
-        });
-    } else {
-        constexpr int UN = 2 * DW;
-        for (int c0 = 0; c0 < nchunks; c0 += UN)
-            static_for<0, UN>([&](auto ic) {
-                constexpr int u = decltype(ic)::value;
-                if (c0 + u < nchunks) {
-                    issue_w(SSD_WSLOT(u + DW - 1), c0 + u + DW - 1);
-                    multiply(SSD_WSLOT(u), u & 1);
-                    __syncthreads();
-                }
-            });
-    }
-#undef SSD_WSLOT
-    if (DBG & 4) {
-        float sum = 0.f;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sum += acc[mt][i];
-        if (sum == 1.2345f) *(float*)outv = sum;
-        return;
-    }
-    const bool lead = wk == 0;
-    if (WK > 1) {
-        float* red = (float*)smem_u4;
-        constexpr int VALS = MT * 16;
-        if (!lead) {
-            float* dst = red + ((size_t)((wk - 1) * WN + wn) * VALS) * 64 + lane;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[mt][i];
-        }
-        __syncthreads();
-        if (lead) {
-#pragma unroll
-            for (int w2 = 1; w2 < WK; ++w2) {
-                const float* src = red + ((size_t)((w2 - 1) * WN + wn) * VALS) * 64 + lane;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[mt][i] += src[(mt * 16 + i) * 64];
-            }
-        }
-    }
-    if (EPI == EPI_F32) {
-        float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
-        if (lead && nt_ok0) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = m0 + mt * 32 + lm;
-                if (m >= M) continue;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nt0 * 32 + g * 8 + lh * 4;
-                    *(float4*)(out + (size_t)m * N + n) =
-                        make_float4(acc[mt][g * 4], acc[mt][g * 4 + 1], acc[mt][g * 4 + 2], acc[mt][g * 4 + 3]);
-                }
-            }
-        }
-    } else if (EPI == EPI_SWIGLU) {
-        float* xch = (float*)smem_u4;
-        if (WK > 1) __syncthreads();
-        if (lead && (wn & 1)) {
-            float* dst = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[mt][i];
-        }
-        __syncthreads();
-        bf16_t* out = (bf16_t*)outv;
-        if (lead && !(wn & 1) && nt_ok0) {
-            const float* src = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = m0 + mt * 32 + lm;
-                if (m >= M) continue;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int f = nt0 * 32 + g * 8 + lh * 4;
-                    uint16_t o[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float gv = acc[mt][g * 4 + j], uv = src[(mt * 16 + g * 4 + j) * 64];
-                        o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
-                    }
-                    *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
-                        make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                }
-            }
-        }
-    } else if (lead) {
-        float* out = (float*)outv;
-        const int tile_out = blockIdx.x * WN + wn;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            float bm = -INFINITY;
-            int bi = 0x7fffffff;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int n = nt0 * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                const float v = acc[mt][i];
-                if (n != mask_id && v > bm) { bm = v; bi = n; }
-            }
-            {
-                const float om = __shfl_xor(bm, 32, 64);
-                const int oi = __shfl_xor(bi, 32, 64);
-                if (om > bm || (om == bm && oi < bi)) { bm = om; bi = oi; }
-            }
-            float se = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int n = nt0 * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                if (n != mask_id) se += expf(acc[mt][i] - bm);
-            }
-            se += __shfl_xor(se, 32, 64);
-            const int m = m0 + mt * 32 + lm;
-            if (lh == 0 && m < M && tile_out < n_tiles_out && nt_ok0) {
-                float* o = out + ((size_t)m * n_tiles_out + tile_out) * 3;
-                o[0] = bm;
-                o[1] = __int_as_float(bi);
-                o[2] = se;
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------------
 // launcher
 // ------------------------------------------------------------------------
 static int env_int(const char* name, int dflt) {
@@ -695,7 +528,11 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
                        int up_tile_off, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
     constexpr int KC = WK * 32, ROWS = MT * 32, LDW = KC + 8;
     constexpr size_t xbytes = (size_t)3 * ROWS * LDW * 2 + (size_t)WN * WK * 64 * 16;   // three stages + spare slots
-    constexpr size_t rbytes = WK > 1 ? (size_t)(WK - 1) * WN * R * MT * 16 * 64 * 4 : (size_t)(WN / 2 + 1) * MT * 16 * 64 * 4;
+    // epilogue exchange areas: see the kernel's epilogues
+    constexpr size_t rbytes = (WK == 2 && R == 1 && EPI == EPI_F32)      ? (size_t)WN * 2 * MT * 2 * 1024
+                              : (WK == 2 && R == 1 && EPI == EPI_SWIGLU) ? (size_t)(WN / 2) * 12 * MT * 1024
+                              : WK > 1 ? (size_t)(WK - 1) * WN * R * MT * 16 * 64 * 4
+                                       : (size_t)(WN / 2 + 1) * MT * 16 * 64 * 4;
     constexpr size_t smem = xbytes > rbytes ? xbytes : rbytes;
     static_assert(smem <= 160 * 1024, "LDS budget");
     auto kern = k_gemm_mfma<WN, WK, R, MT, EPI, NCH>;
@@ -708,7 +545,7 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
     const int tiles = EPI == EPI_SWIGLU ? up_tile_off : N / 32;
     const int per_wg = EPI == EPI_SWIGLU ? (R == 2 ? WN : WN / 2) : WN * R;
     dim3 grid((tiles + per_wg - 1) / per_wg, m_chunks, split);
-    hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K / split, split_stride,
+    hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K, K / split, split_stride,
                        up_tile_off, mask_id, n_tiles_out);
     return true;
 }

@@ -106,8 +106,16 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave % WN, wk = wave / WN;
     const int lm = lane & 31, lh = lane >> 5;
+    // Work-groups go to the 8 XCDs round-robin by their linear id.  With split-K the low bits of
+    // blockIdx.x pick the k-slice, so the work-groups of one XCD read the same slice of the
+    // activations and find it in that XCD's L2; the n-block takes the remaining bits.
+    int bx = blockIdx.x, bz = blockIdx.z;
+    if (gridDim.z > 1 && gridDim.x % gridDim.z == 0) {
+        bz = blockIdx.x % gridDim.z;
+        bx = blockIdx.x / gridDim.z + (gridDim.x / gridDim.z) * blockIdx.z;
+    }
     const int m0 = blockIdx.y * ROWS;
-    const int kbeg = blockIdx.z * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
+    const int kbeg = bz * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
     const int KS = K >> 4, NT = N >> 5;
 
     // n-tiles of this wave.  SwiGLU pairs the gate tile of 32 channels with their up tile
@@ -115,7 +123,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
     int nt[R];
     bool nt_ok[R];
     if (EPI == EPI_SWIGLU) {
-        const int ch = R == 2 ? blockIdx.x * WN + wn : blockIdx.x * (WN / 2) + (wn >> 1);
+        const int ch = R == 2 ? bx * WN + wn : bx * (WN / 2) + (wn >> 1);
         const bool ok = ch < up_tile_off;
         const int chc = ok ? ch : up_tile_off - 1;
 #pragma unroll
@@ -126,7 +134,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
     } else {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            nt[r] = (blockIdx.x * WN + wn) * R + r;
+            nt[r] = (bx * WN + wn) * R + r;
             nt_ok[r] = nt[r] < NT;
             if (!nt_ok[r]) nt[r] = NT - 1;
         }
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[r][mt][i] = 0.f;
 
-    const int rot = (int)((blockIdx.x * 5u + blockIdx.z * 3u) % (unsigned)nchunks);
+    const int rot = (int)((bx * 5u + bz * 3u) % (unsigned)nchunks);
     auto chunk_at = [&](int c) {
         c = c < nchunks - 1 ? c : nchunks - 1;
         c += rot;
@@ -296,7 +304,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
             }
         });
         __syncthreads();
-        float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
+        float* out = (float*)outv + (size_t)bz * split_stride;
         static_for<0, 2>([&](auto iw) {
             constexpr int w = decltype(iw)::value;
             if (wk == w && nt_ok[0]) {
@@ -342,7 +350,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         });
         __syncthreads();
         bf16_t* out = (bf16_t*)outv;
-        const int ch = blockIdx.x * (WN / 2) + pr;
+        const int ch = bx * (WN / 2) + pr;
         static_for<0, 4>([&](auto iq) {
             constexpr int me = decltype(iq)::value;
             if (q == me && ch < up_tile_off) {
@@ -403,7 +411,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 
     // ---- epilogues.  Lane (lm, lh) holds, per tile, rows n = 8*(i/4) + 4*lh + i%4 of column m = lm.
     if (EPI == EPI_F32) {
-        float* out = (float*)outv + (size_t)blockIdx.z * split_stride;
+        float* out = (float*)outv + (size_t)bz * split_stride;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (!lead || !nt_ok[r]) continue;
@@ -480,7 +488,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         float* out = (float*)outv;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int tile_out = (blockIdx.x * WN + wn) * R + r;
+            const int tile_out = (bx * WN + wn) * R + r;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 float bm = -INFINITY;

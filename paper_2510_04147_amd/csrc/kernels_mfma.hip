@@ -526,11 +526,6 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 // ------------------------------------------------------------------------
 // launcher
 // ------------------------------------------------------------------------
-static int env_int(const char* name, int dflt) {
-    const char* s = getenv(name);
-    return s ? atoi(s) : dflt;
-}
-
 template <int WN, int WK, int R, int MT, int EPI, int NCH>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
                        int up_tile_off, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
@@ -635,11 +630,29 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
         *n_split = lm_tiles_mfma(N);
         return launch_nch<WN, WK, 1, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
     }
-    int want = N <= 8192 ? env_int("SSD_SPLIT_SMALLN", 8) : env_int("SSD_SPLIT_LARGEN", 2);
+    // Work-group shape and split along K: functions of the weight shape alone, chosen so that the
+    // grid comes close to one work-group per CU (256) with at least 16 K chunks each where the
+    // shape allows.  Wide outputs (the QKV projection): n-blocks of 96 rows, two k-slices; narrow
+    // outputs with a short K (the attention output projection): 64 rows, four k-slices; narrow
+    // outputs with a long K (the down projection): 128 rows, eight k-slices.
+    int wn, want;
+    if (N > 8192) {
+        wn = (N / 32) % 3 == 0 ? 3 : 4;
+        want = 2;
+    } else if (K <= 4096) {
+        wn = 2;
+        want = 4;
+    } else {
+        wn = 4;
+        want = 8;
+    }
     if (want > SSD_MAX_SPLIT) want = SSD_MAX_SPLIT;
     const int split = pick_split(K, KC, want);
     *n_split = split;
-    return launch_nch<WN, WK, 1, EPI_F32>(K / split / KC, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    const int nch = K / split / KC;
+    if (wn == 3) return launch_nch<3, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    if (wn == 2) return launch_nch<2, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    return launch_nch<WN, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
 }
 #endif
 

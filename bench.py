@@ -6,7 +6,8 @@ A "step" is one pass of the whole hot path: one batched verification forward
 8B-class workload (prompt 256, block 32, draft depth 4 -> 5 nodes, M = 160 rows)
 against a cached prefix of S = 384 positions (the middle of the 256..480 range
 the workload sweeps).  Inputs, weights and the prefix KV are resident in HBM
-before the timed region.
+before the timed region.  --workload selects another configuration (the default
+prefix is then prompt + half the generation length, for every sequence of the batch).
 
 Prints ONE JSON line.  `value` is generated tokens/s of a complete
 ssd_generate run of the same workload (prompt prefill and KV-append passes
@@ -26,6 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0        # dense bf16
 
 
 def read_measured_traffic(workload):
@@ -50,7 +52,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug only; marks the line invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-generate", action="store_true")
-    ap.add_argument("--prefix", type=int, default=384)
+    ap.add_argument("--prefix", type=int, default=0, help="cached prefix length of the timed forward "
+                    "(default: prompt + half the generation length)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy, the known-size kernel that scales rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters")
@@ -68,8 +71,9 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     over = {"n_layers": args.layers} if args.layers else {}
     cfg = synth.model_config(wl["model"], **over)
-    B, N, P, G = wl["block"], wl["draft"], wl["prompt_len"], wl["gen_len"]
-    assert wl["batch"] == 1, "the bench line is the batch-1 workload"
+    B, N, P, G, nseq = wl["block"], wl["draft"], wl["prompt_len"], wl["gen_len"], wl["batch"]
+    S = args.prefix if args.prefix > 0 else P + G // 2
+    assert S + B <= P + G, "the timed forward must fit the sequence"
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -78,19 +82,21 @@ def main():
     torch.cuda.synchronize()                 # the library reads the weights on its own stream
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=P + G, block=B, max_draft=N, max_rows=max(P, args.prefix, (N + 1) * B))
-        # ---- verification forward at prefix S, fixed block state with N drafts
-        S = args.prefix
-        note(f"context created; prefill of {S} positions")
-        prefix = synth.gen_prompt(cfg, wl["seed"], S)
-        eng.prefill_kv(0, prefix, 0)
+        eng = binding.SSD(cfg, wg, max_seqs=nseq, max_seq_len=P + G, block=B, max_draft=N,
+                          max_rows=max(P, S, nseq * (N + 1) * B))
+        # ---- verification forward at prefix S, fixed block state with N drafts, every sequence of the batch
+        note(f"context created; prefill of {nseq} x {S} positions")
+        for i in range(nseq):
+            eng.prefill_kv(i, synth.gen_prompt(cfg, wl["seed"] + i, S), 0)
         tok = [cfg["mask_id"]] * B
         masked = (1 << B) - 1
-        drafts = [(3 + 5 * i, 100 + i) for i in range(N)]
-        out = eng.new_out(1)
+        drafts = [((3 + 5 * i) % B, 100 + i) for i in range(N)]
+        assert len({q for q, _ in drafts}) == N, "draft positions must differ"
+        out = eng.new_out(nseq)
+        seqs = list(range(nseq))
 
         def step():
-            eng.verify_tree([0], [tok], [masked], [S], [drafts], N, out)
+            eng.verify_tree(seqs, [tok] * nseq, [masked] * nseq, [S] * nseq, [drafts] * nseq, N, out)
 
         stream.synchronize()
         note("warm-up verification forwards")
@@ -108,6 +114,14 @@ def main():
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         ms_step = e0.elapsed_time(e1) / args.steps
+        # median over the same number of forwards, one event pair each (a separate pass)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in evs:
+            a.record(stream)
+            step()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms_median = float(np.median([a.elapsed_time(b) for a, b in evs]))
 
         if args.copy_calibration:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -149,45 +163,61 @@ def main():
         gen = {}
         if not args.no_generate:
             note("full generation: SSD, then stepwise")
-            prompt = synth.gen_prompt(cfg, wl["seed"], P)
-            eng.generate([prompt], B, B, N)                      # warm
-            toks_ssd, st_ssd = eng.generate([prompt], G, B, N)
-            toks_step, st_step = eng.generate([prompt], G, B, 0)
+            prompts = [synth.gen_prompt(cfg, wl["seed"] + i, P) for i in range(nseq)]
+            eng.generate(prompts, B, B, N)                       # warm
+            toks_ssd, st_ssd = eng.generate(prompts, G, B, N)
+            toks_step, st_step = eng.generate(prompts, G, B, 0)
             same = bool(np.array_equal(toks_ssd, toks_step))
+            GT = G * nseq                                        # tokens generated over the whole batch
             gen = dict(
-                ssd_tokens_per_s=G / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=G / (st_step["total_ms"] / 1e3),
+                ssd_tokens_per_s=GT / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_step["total_ms"] / 1e3),
                 ssd_forwards=st_ssd["forwards"], stepwise_forwards=st_step["forwards"], kv_passes=st_ssd["kv_passes"],
-                accepted_per_forward=G / st_ssd["forwards"], accept_hist=st_ssd["accept_hist"][:N + 2],
+                accepted_per_forward=GT / max(sum(st_ssd["accept_hist"]), 1), accept_hist=st_ssd["accept_hist"][:N + 2],
                 ssd_decode_ms_per_forward=st_ssd["decode_ms"] / st_ssd["forwards"],
                 stepwise_ms_per_forward=st_step["decode_ms"] / st_step["forwards"],
                 ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"])
 
     # ---- roofline arithmetic
-    M = (N + 1) * B
+    M = nseq * (N + 1) * B
     params = synth.streamed_param_count(cfg)
     esz = 2 if cfg["dtype"] == "bf16" else 4
-    bytes_fwd = params * esz + S * synth.kv_bytes_per_token(cfg)
+    bytes_fwd = params * esz + nseq * S * synth.kv_bytes_per_token(cfg)
+    flops_fwd = 2.0 * M * params + 4.0 * M * (S + B) * cfg["n_q_heads"] * cfg["head_dim"] * cfg["n_layers"]
     fwd_gbs = bytes_fwd / (ms_step * 1e-3) / 1e9
+    fwd_tflops = flops_fwd / (ms_step * 1e-3) / 1e12
     d, F = cfg["d_model"], cfg["d_ffn"]
     gu = prof.get("gemm_gate_up_swiglu", dict(launches=0, ms=0.0))
     gu_bytes = 2 * F * d * esz + M * d * esz + M * F * esz     # weights + activations in + SwiGLU out
+    gu_flops = 2.0 * M * 2 * F * d
     gu_us = 1e3 * gu["ms"] / max(gu["launches"], 1)
     gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9 if gu_us > 0 else 0.0
+    gu_tflops = gu_flops / (gu_us * 1e-6) / 1e12 if gu_us > 0 else 0.0
     traffic = read_measured_traffic(args.workload)
+    # the bound is whichever of the two rooflines takes longer for this kernel's bytes and flops
+    hbm_bound = gu_bytes / (HBM_PEAK_GBS * 1e9) >= gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_bound:
+        roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"]}
+    else:
+        roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": gu_tflops,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": traffic, "flops_per_launch": gu_flops, "achieved_GBs": gu_gbs, "us_per_launch": gu_us,
+                "launches_timed": gu["launches"]}
     line = {
         "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
         "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
-        "config": {"workload": args.workload, "model": wl["model"], "n_layers": cfg["n_layers"], "batch": 1,
+        "config": {"workload": args.workload, "model": wl["model"], "n_layers": cfg["n_layers"], "batch": nseq,
                    "prompt_len": P, "gen_len": G, "block": B, "draft_depth": N, "rows_per_forward": M,
                    "prefix_len_timed": S},
-        "roofline": {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"]},
+        "roofline": roof,
         "forward": {"bytes_per_forward": bytes_fwd, "achieved_GBs": fwd_gbs, "frac_of_hbm_peak": fwd_gbs / HBM_PEAK_GBS,
+                    "flops_per_forward": flops_fwd, "achieved_TFLOPs": fwd_tflops,
+                    "frac_of_mfma_peak": fwd_tflops / MFMA_BF16_PEAK_TFLOPS,
                     "hbm_streaming_read_ceiling_GBs": ceil_gbs, "frac_of_streaming_ceiling": fwd_gbs / ceil_gbs,
-                    "host_wall_ms_per_step": wall_ms,
+                    "ms_per_step_median": ms_median, "host_wall_ms_per_step": wall_ms,
                     "kernel_classes_us_per_forward": {k: 1e3 * v["ms"] / n_prof for k, v in prof.items()}},
         "generate": gen,
     }

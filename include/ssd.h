@@ -192,6 +192,14 @@ int ssd_generate(ssd_ctx* ctx, int n, const int32_t* const* prompts, const int* 
  * available (bf16).  Default 1.  Returns the previous value or an error. */
 int ssd_set_kernel_path(ssd_ctx* ctx, int path);
 
+/* Block-boundary fusion in ssd_generate (Section 3.1: blocks are decoded in
+ * order, each against the cache of all earlier ones): 1 = the KV append of a
+ * finished block and the block-start draft of the next block share one
+ * forward (one weight pass instead of two per block), 0 = separate forwards.
+ * The generated tokens are the same either way.  Default 1.  Returns the
+ * previous value or an error. */
+int ssd_set_boundary_fusion(ssd_ctx* ctx, int on);
+
 /* Per-kernel-class timing with HIP events on the context's stream.
  * ssd_profile_begin() turns it on and clears the counters; ssd_profile_read()
  * synchronises the stream and fills, for class c < *n_classes: launches[c],

@@ -63,14 +63,6 @@ __global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restr
         row_pos[row] = nd.S + p;
         row_node[row] = ni;
     }
-    if (g.mode == GM_DECODE && g.fresh && nd.j == 0) {
-        // a fresh block: every position masked, no drafts (Algorithm 1, line 3)
-        for (int p = threadIdx.x; p < SSD_MAX_BLOCK; p += blockDim.x) s->tok[p] = mask_id;
-        if (threadIdx.x == 0) {
-            s->masked = nd.blen >= 64 ? ~0ull : ((1ull << nd.blen) - 1ull);
-            s->n_draft = 0;
-        }
-    }
 }
 
 // a1: embedding gather into the fp32 residual stream.
@@ -498,7 +490,7 @@ __global__ __launch_bounds__(256) void k_lm_merge(const float* __restrict__ part
 __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
                                                const float* __restrict__ row_conf, const int* __restrict__ row_arg,
                                                const float* __restrict__ row_max, StepResult* __restrict__ result,
-                                               ssd_step_out out, int blockB, int maxDraft) {
+                                               ssd_step_out out, int blockB, int maxDraft, int mask_id) {
     const int gi = blockIdx.x, lane = threadIdx.x;
     const GroupDesc g = fw->groups[gi];
     if (g.mode != GM_DECODE) return;
@@ -507,7 +499,10 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     const int blen = g.blen;
     const int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
     const int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
-    unsigned long long cur = s->masked;
+    // a fresh block starts all masked with no drafts (Algorithm 1, line 3); its state is written here,
+    // at the end of the forward, so that a KV-append group of the same sequence in the same forward
+    // still reads the finished block's tokens
+    unsigned long long cur = g.fresh ? (blen >= 64 ? ~0ull : ((1ull << blen) - 1ull)) : s->masked;
     __syncthreads();
 
     if (lane < blen) {
@@ -563,6 +558,8 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         if (out.next_pos) out.next_pos[(size_t)gi * maxDraft + rank] = lane;
         if (out.next_tok) out.next_tok[(size_t)gi * maxDraft + rank] = my_tok;
     }
+    if (g.fresh) s->tok[lane] = mask_id;                  // SSD_MAX_BLOCK = 64 = one lane per position
+    __syncthreads();
     if (lane <= m) {
         const int ap = lane < m ? my_dpos : pstar;
         const int at = lane < m ? my_dtok : tstar;
@@ -671,7 +668,7 @@ void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipS
     ssd_step_out o = {};
     if (out) o = *out;
     k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result, o,
-                                      c->dm.block, c->dm.max_draft);
+                                      c->dm.block, c->dm.max_draft, c->dm.mask_id);
 }
 
 // Helpers of the kernel-level entry points.

@@ -185,6 +185,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     }
     c->embed = w->embed; c->final_norm = w->final_norm;
     c->kernel_path = 1;
+    c->fuse_boundary = 1;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
     memset(c->prof_ms, 0, sizeof c->prof_ms); memset(c->prof_n, 0, sizeof c->prof_n);
@@ -259,6 +260,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_kernel_path(ssd_ct
     if (!c || (path != 0 && path != 1)) return SSD_EINVAL;
     const int old = c->kernel_path;
     c->kernel_path = path;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_boundary_fusion(ssd_ctx* c, int on) {
+    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
+    const int old = c->fuse_boundary;
+    c->fuse_boundary = on;
     return old;
 }
 
@@ -575,6 +583,25 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
         FwdHeader hd;
         memset(&hd, 0, sizeof hd);
         bool any_decode = false;
+        // Block-boundary fusion: the KV append of a finished block and the block-start draft of the
+        // next block of the same sequence share one forward.  The append node's keys and values
+        // reach the cache in each layer's rotary kernel, before that layer's attention kernel, so the
+        // next block's node simply reads a prefix that is one block longer.  Fused only while the
+        // forward still fits max_rows.
+        bool fuse[SSD_MAX_SEQS] = {};
+        if (c->fuse_boundary) {
+            int rows = 0;
+            for (int i = 0; i < n; ++i) {
+                if (phase[i] == DONE) continue;
+                const int bl = std::min(block, gen_len - blk[i] * block);
+                rows += phase[i] == APPEND ? bl : ((phase[i] == FRESH ? 0 : n_dr[i]) + 1) * bl;
+            }
+            for (int i = 0; i < n; ++i) {
+                if (phase[i] != APPEND || blk[i] + 1 >= n_blocks) continue;
+                const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
+                if (rows + bln <= d.max_rows) { fuse[i] = true; rows += bln; }
+            }
+        }
         for (int pass = 0; pass < 2; ++pass)          // decode groups first, then KV appends
             for (int i = 0; i < n; ++i) {
                 if (phase[i] == DONE) continue;
@@ -582,6 +609,12 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
                 if (pass == 0 && phase[i] != APPEND) {
                     if (phase[i] == FRESH) { n_masked[i] = bl; n_dr[i] = 0; }
                     add_group(hd, i, GM_DECODE, bl, c->cached_len[i], n_dr[i] + 1, draft_depth, phase[i] == FRESH, 0, -1);
+                    any_decode = true;
+                } else if (pass == 0 && fuse[i]) {
+                    const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
+                    n_masked[i] = bln;
+                    n_dr[i] = 0;
+                    add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, draft_depth, 1, 0, -1);
                     any_decode = true;
                 } else if (pass == 1 && phase[i] == APPEND) {
                     add_group(hd, i, GM_APPEND, bl, c->cached_len[i], 1, 0, 0, 0, blk[i] * block);
@@ -613,7 +646,8 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
             } else {
                 c->cached_len[i] += g.blen;
                 blk[i]++;
-                if (blk[i] == n_blocks) { phase[i] = DONE; live--; } else phase[i] = FRESH;
+                if (blk[i] == n_blocks) { phase[i] = DONE; live--; }
+                else if (!fuse[i]) phase[i] = FRESH;     // a fused sequence is already decoding its next block
             }
         }
     }

@@ -151,6 +151,7 @@ struct ssd_ctx {
     int part_cols;             // columns of one split-K partial buffer = max(d, nqkv)
     hipStream_t stream;
     int kernel_path;
+    int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
     int cached_len[SSD_MAX_SEQS];
     // host staging ring for descriptors / small uploads
     static const int kSlots = 4;

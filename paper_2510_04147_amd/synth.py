@@ -39,6 +39,10 @@ WORKLOADS = {
     "cfg3_8b_b64_n8": dict(model="8b", batch=1, prompt_len=512, gen_len=512, block=64, draft=8, seed=1003),
     "cfg4_8b_batch4": dict(model="8b", batch=4, prompt_len=1024, gen_len=256, block=32, draft=4, seed=1004),
     "cfg5_7b_gqa_batch8": dict(model="7b_gqa", batch=8, prompt_len=512, gen_len=256, block=32, draft=8, seed=1005),
+    # the paper's own decoding shape (Section 4.1: block 8, draft length 3 to 5), reported for context
+    "ctx_8b_b8_n3": dict(model="8b", batch=1, prompt_len=256, gen_len=256, block=8, draft=3, seed=1006),
+    "ctx_8b_b8_n4": dict(model="8b", batch=1, prompt_len=256, gen_len=256, block=8, draft=4, seed=1006),
+    "ctx_8b_b8_n5": dict(model="8b", batch=1, prompt_len=256, gen_len=256, block=8, draft=5, seed=1006),
 }
 
 

@@ -90,6 +90,25 @@ def test_generate_ssd_equals_stepwise_and_oracle(setup):
     print("forwards oracle/gpu:", so["forwards"], sg["forwards"], sg["accept_hist"][:6])
 
 
+def test_block_boundary_fusion_changes_passes_not_tokens(setup):
+    """The KV append of a finished block rides in the next block's first forward: same tokens and
+    the same number of decode forwards, one KV-only pass per sequence instead of one per block."""
+    cfg, w, wg, eng = setup
+    prompt = synth.gen_prompt(cfg, 77, 40)
+    try:
+        for N in (0, 3):
+            assert eng.set_boundary_fusion(0) == 1
+            sep, st_sep = eng.generate([prompt], 72, 16, N)          # 5 blocks, the last one short
+            assert eng.set_boundary_fusion(1) == 0
+            fus, st_fus = eng.generate([prompt], 72, 16, N)
+            assert np.array_equal(sep, fus)
+            assert st_sep["forwards"] == st_fus["forwards"] and st_sep["accept_hist"] == st_fus["accept_hist"]
+            assert st_sep["kv_passes"] == 1 + 5 and st_fus["kv_passes"] == 1 + 1
+        exempt_or_equal(cfg, w, prompt, 72, 16, fus[0])
+    finally:
+        eng.set_boundary_fusion(1)
+
+
 def test_generate_batch_of_two_ragged(setup):
     cfg, w, wg, eng = setup
     p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)

@@ -200,6 +200,16 @@ int ssd_set_kernel_path(ssd_ctx* ctx, int path);
  * previous value or an error. */
 int ssd_set_boundary_fusion(ssd_ctx* ctx, int on);
 
+/* HIP graphs: 1 = the kernel sequence of a forward is captured the second time
+ * a launch shape (row count, node count, block length) occurs and replayed from
+ * then on; 0 = every forward launches its kernels one by one.  Results are the
+ * same; a context keeps at most 64 graphs and runs further shapes ungraphed,
+ * as it does every forward of a context on the default (NULL) stream, which
+ * cannot be captured.  Default 0: on MI355X a replayed graph of the ~270 dependent
+ * kernels of an 8B forward took the same time as launching them one by one (the
+ * host stays ahead of the GPU either way).  Returns the previous value or an error. */
+int ssd_set_graphs(ssd_ctx* ctx, int on);
+
 /* Per-kernel-class timing with HIP events on the context's stream.
  * ssd_profile_begin() turns it on and clears the counters; ssd_profile_read()
  * synchronises the stream and fills, for class c < *n_classes: launches[c],

@@ -490,9 +490,10 @@ __global__ __launch_bounds__(256) void k_lm_merge(const float* __restrict__ part
 __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
                                                const float* __restrict__ row_conf, const int* __restrict__ row_arg,
                                                const float* __restrict__ row_max, StepResult* __restrict__ result,
-                                               ssd_step_out out, int blockB, int maxDraft, int mask_id) {
+                                               int blockB, int maxDraft, int mask_id) {
     const int gi = blockIdx.x, lane = threadIdx.x;
     const GroupDesc g = fw->groups[gi];
+    const ssd_step_out out = fw->out;
     if (g.mode != GM_DECODE) return;
     SeqState* s = &state[g.seq];
     const int nd = g.n_nodes - 1;
@@ -664,10 +665,8 @@ void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
                                  c->dm.mask_id);
 }
 
-void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st) {
-    ssd_step_out o = {};
-    if (out) o = *out;
-    k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result, o,
+void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st) {
+    k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result,
                                       c->dm.block, c->dm.max_draft, c->dm.mask_id);
 }
 

@@ -186,6 +186,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->embed = w->embed; c->final_norm = w->final_norm;
     c->kernel_path = 1;
     c->fuse_boundary = 1;
+    c->use_graphs = 0;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
     memset(c->prof_ms, 0, sizeof c->prof_ms); memset(c->prof_n, 0, sizeof c->prof_n);
@@ -239,6 +240,8 @@ extern "C" __attribute__((visibility("default"))) int ssd_destroy(ssd_ctx* c) {
     }
     if (c->host_result) (void)hipHostFree(c->host_result);
     for (auto ev : c->ev_pool) (void)hipEventDestroy(ev);
+    for (auto& g : c->graphs)
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
     delete c;
     return SSD_OK;
 }
@@ -267,6 +270,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_boundary_fusion(ss
     if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
     const int old = c->fuse_boundary;
     c->fuse_boundary = on;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_graphs(ssd_ctx* c, int on) {
+    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
+    const int old = c->use_graphs;
+    c->use_graphs = on;
     return old;
 }
 
@@ -370,6 +380,7 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     if (c->stage_used[slot]) HIPCHK(c, hipEventSynchronize(c->stage_ev[slot]));
     char* sp = c->stage[slot];
     memcpy(sp, &hd, sizeof hd);
+    if (out) ((FwdHeader*)sp)->out = *out;
     HIPCHK(c, hipMemcpyAsync(c->b.fwd, sp, sizeof hd, hipMemcpyHostToDevice, st));
     if (n_raw > 0) {
         int* sr = (int*)(sp + sizeof(FwdHeader));
@@ -389,37 +400,76 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     const int M = hd.M, ML = hd.M_logits;
     int max_blen = 0;
     for (int i = 0; i < hd.n_nodes; ++i) max_blen = std::max(max_blen, hd.nodes[i].blen);
-    {
-        ProfScope ps(c, KC_ROWS);
-        launch_build_rows(c, st, hd.n_nodes);
-        launch_embed(c, M, st);
-    }
-    int n_part = 0, ns = 1;
-    for (int l = 0; l < d.L; ++l) {
-        const LayerW& w = c->lw[l];
-        { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
-        n_part = 0;
-        gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.part, M, &ns);
-        { ProfScope ps(c, KC_ROPE); launch_rope(c, hd.n_nodes, max_blen, l, ns, st); }
-        if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
+
+    // ---- the kernel sequence: a function of (M, ML, n_nodes, n_groups, max_blen, kernel path) only
+    auto launch_all = [&]() {
         {
-            ProfScope ps(c, KC_ATTN);
-            if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, hd.n_nodes, max_blen, l, st)))
-                launch_attn_plain(c, M, l, st);
+            ProfScope ps(c, KC_ROWS);
+            launch_build_rows(c, st, hd.n_nodes);
+            launch_embed(c, M, st);
         }
-        gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);
-        { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm2, ns, st); }
-        gemm(c, KC_GEMM_GU, EPI_SWIGLU, c->b.xn, w.wgu, c->b.act, M, &ns);
-        gemm(c, KC_GEMM_DOWN, EPI_F32, c->b.act, w.wdown, c->b.part, M, &ns);
-        n_part = ns;
+        int n_part = 0, ns = 1;
+        for (int l = 0; l < d.L; ++l) {
+            const LayerW& w = c->lw[l];
+            { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
+            n_part = 0;
+            gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.part, M, &ns);
+            { ProfScope ps(c, KC_ROPE); launch_rope(c, hd.n_nodes, max_blen, l, ns, st); }
+            if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
+            {
+                ProfScope ps(c, KC_ATTN);
+                if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, hd.n_nodes, max_blen, l, st)))
+                    launch_attn_plain(c, M, l, st);
+            }
+            gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);
+            { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm2, ns, st); }
+            gemm(c, KC_GEMM_GU, EPI_SWIGLU, c->b.xn, w.wgu, c->b.act, M, &ns);
+            gemm(c, KC_GEMM_DOWN, EPI_F32, c->b.act, w.wdown, c->b.part, M, &ns);
+            n_part = ns;
+        }
+        if (ML > 0) {
+            { ProfScope ps(c, KC_NORM); launch_norm(c, ML, c->final_norm, n_part, st); }
+            int tiles = 0;
+            gemm(c, KC_LMHEAD, EPI_LMHEAD, c->b.xn, c->lm_head, c->b.lm_part, ML, &tiles);
+            { ProfScope ps(c, KC_LMMERGE); launch_lm_merge(c, ML, tiles, st); }
+            { ProfScope ps(c, KC_ACCEPT); launch_accept(c, hd.n_groups, st); }
+        }
+    };
+
+    ssd_ctx::FwdGraph* fg = nullptr;
+    if (c->use_graphs && !c->profiling && st != nullptr) {      // the legacy default stream cannot be captured
+        for (auto& g : c->graphs)
+            if (g.M == M && g.ML == ML && g.n_nodes == hd.n_nodes && g.n_groups == hd.n_groups &&
+                g.max_blen == max_blen && g.kernel_path == c->kernel_path) { fg = &g; break; }
+        if (!fg && c->graphs.size() < 64) {
+            c->graphs.push_back({M, ML, hd.n_nodes, hd.n_groups, max_blen, c->kernel_path, 0, nullptr});
+            fg = &c->graphs.back();
+        }
     }
-    if (ML > 0) {
-        { ProfScope ps(c, KC_NORM); launch_norm(c, ML, c->final_norm, n_part, st); }
-        int tiles = 0;
-        gemm(c, KC_LMHEAD, EPI_LMHEAD, c->b.xn, c->lm_head, c->b.lm_part, ML, &tiles);
-        { ProfScope ps(c, KC_LMMERGE); launch_lm_merge(c, ML, tiles, st); }
-        { ProfScope ps(c, KC_ACCEPT); launch_accept(c, hd.n_groups, out, st); }
+    if (fg && fg->exec) {
+        HIPCHK(c, hipGraphLaunch(fg->exec, st));
+        return SSD_OK;
     }
+    if (fg && fg->seen >= 1) {
+        // second forward of this shape: every kernel it launches has run once (function attributes
+        // are set), so the sequence can be recorded.  A failed capture leaves the shape eager.
+        hipGraph_t graph = nullptr;
+        if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+            launch_all();
+            hipError_t e = hipStreamEndCapture(st, &graph);
+            if (e == hipSuccess && graph && hipGraphInstantiate(&fg->exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+                (void)hipGraphDestroy(graph);
+                HIPCHK(c, hipGraphLaunch(fg->exec, st));
+                return SSD_OK;
+            }
+            if (graph) (void)hipGraphDestroy(graph);
+            fg->exec = nullptr;
+        }
+        (void)hipGetLastError();                     // a refused capture must not poison later error checks
+        fg->seen = -1;                               // do not try again
+    }
+    launch_all();
+    if (fg && fg->seen >= 0) fg->seen++;
     HIPCHK(c, hipGetLastError());
     return SSD_OK;
 }

@@ -37,6 +37,7 @@ struct NodeDesc {
 
 struct FwdHeader {
     int n_groups, n_nodes, M, M_logits;
+    ssd_step_out out;            // where the acceptance kernel writes a step call's outputs (null pointers: nowhere)
     GroupDesc groups[SSD_MAX_SEQS];
     NodeDesc nodes[SSD_MAX_NODES];
 };
@@ -152,6 +153,16 @@ struct ssd_ctx {
     hipStream_t stream;
     int kernel_path;
     int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
+    // HIP graphs of the forward's kernel sequence, one per launch shape.  Everything that changes
+    // between forwards of one shape (tokens, prefix lengths, drafts, output pointers) lives in
+    // device memory, so a shape's second forward is captured and later ones replay the graph.
+    int use_graphs;
+    struct FwdGraph {
+        int M, ML, n_nodes, n_groups, max_blen, kernel_path;
+        int seen;
+        hipGraphExec_t exec;
+    };
+    std::vector<FwdGraph> graphs;
     int cached_len[SSD_MAX_SEQS];
     // host staging ring for descriptors / small uploads
     static const int kSlots = 4;
@@ -179,7 +190,7 @@ void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStre
 void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t st);
 void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st);
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
-void launch_accept(const ssd_ctx* c, int n_groups, const ssd_step_out* out, hipStream_t st);
+void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st);
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);
 int lm_tiles_plain(int V);
 // out[M,N] = sum over the first n_part split-K partial buffers, in split order

@@ -109,6 +109,58 @@ def test_block_boundary_fusion_changes_passes_not_tokens(setup):
         eng.set_boundary_fusion(1)
 
 
+def test_graph_replays_match_eager_launches(setup):
+    """A launch shape's forward is captured into a HIP graph the second time it occurs and replayed
+    afterwards.  Every replay, with the program's own eager work and synchronisations in between and
+    with different tokens, drafts, prefix lengths and output buffers, must equal the ungraphed run."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    B, N = 32, 4
+    prompt = synth.gen_prompt(cfg, 91, 48)
+    rng = np.random.default_rng(5)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()                                     # the default stream cannot be captured
+    with torch.cuda.stream(stream):
+        eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=256, block=32, max_draft=8, max_rows=9 * 32)
+    calls = []
+    for i in range(6):
+        tok = rng.integers(0, cfg["vocab"] - 1, B).tolist()
+        masked = int(rng.integers(1, 1 << 32)) | 0b11111          # at least five masked positions
+        mpos = [p for p in range(B) if (masked >> p) & 1]
+        masked = sum(1 << p for p in mpos)
+        drafts = [(int(p), int(rng.integers(0, cfg["vocab"] - 1))) for p in rng.permutation(mpos)[:N]]
+        calls.append((tok, masked, drafts))
+
+    def run():
+        res = []
+        eng.reset(0)
+        eng.prefill_kv(0, prompt, 0)
+        for i, (tok, masked, drafts) in enumerate(calls):
+            out = eng.new_out(1)                                     # a new output buffer every call
+            eng.verify_tree([0], [tok], [masked], [48], [drafts], N, out)
+            res.append(out.host())
+            if i == 2:                                               # eager work of another shape in between
+                eng.reset(0)
+                eng.prefill_kv(0, prompt[:40], 0)
+                eng.prefill_kv(0, prompt[40:], 40)
+        gen, st = eng.generate([prompt], 64, 32, 3)
+        return res, gen, st
+
+    try:
+        with torch.cuda.stream(stream):
+            assert eng.set_graphs(0) == 0                            # off by default
+            ref, gen_ref, st_ref = run()
+            assert eng.set_graphs(1) == 0
+            for rep in range(3):                                     # eager, capture, replay; then replays only
+                got, gen, st = run()
+                for a, b in zip(ref, got):
+                    for k in a:
+                        assert np.array_equal(a[k], b[k]), (rep, k)
+                assert np.array_equal(gen, gen_ref) and st["forwards"] == st_ref["forwards"]
+    finally:
+        eng.close()
+
+
 def test_generate_batch_of_two_ragged(setup):
     cfg, w, wg, eng = setup
     p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)

@@ -48,9 +48,13 @@ __device__ __forceinline__ uint16_t f2bf_m(float f) {
 
 // ------------------------------------------------------------------------
 // One-time weight repack: W[N][K] row-major -> fragment order.
-// dst uint4 index ((nt*KS + ks)*64 + lane) holds W[32nt + lane%32][16ks + 8(lane/32) .. +7].
+// dst uint4 index ((nt*KS + ks)*64 + lane) holds row(nt, lane%32), columns [16ks + 8(lane/32), +8).
+// Plain matrices: row(nt, r) = 32nt + r.  The gate/up matrix (F gate rows, then F up rows;
+// gate_rows = F): tile nt holds 16 channels, row(nt, r) = gate row 16nt + r for r < 16 and
+// up row F + 16nt + r - 16 for r >= 16, so that a lane of the 32x32 MFMA result, which holds
+// rows r and r + 16 of a column, holds the gate and the up value of the same channel.
 // ------------------------------------------------------------------------
-__global__ void k_pack_weights(const uint4* __restrict__ src, uint4* __restrict__ dst, int N, int K) {
+__global__ void k_pack_weights(const uint4* __restrict__ src, uint4* __restrict__ dst, int N, int K, int gate_rows) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int KS = K >> 4;
     const size_t total = (size_t)(N >> 5) * KS * 64;
@@ -59,14 +63,15 @@ __global__ void k_pack_weights(const uint4* __restrict__ src, uint4* __restrict_
     const size_t frag = idx >> 6;
     const int ks = (int)(frag % KS);
     const size_t nt = frag / KS;
-    const size_t row = nt * 32 + (lane & 31);
+    const int r = lane & 31;
+    const size_t row = gate_rows > 0 ? (r < 16 ? nt * 16 + r : (size_t)gate_rows + nt * 16 + (r - 16)) : nt * 32 + r;
     const int col = ks * 16 + 8 * (lane >> 5);
     dst[idx] = src[(row * K + col) >> 3];
 }
 
-void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t st) {
+void launch_pack_weights(const void* src, void* dst, int N, int K, int gate_rows, hipStream_t st) {
     const size_t total = (size_t)(N / 32) * (K / 16) * 64;
-    k_pack_weights<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const uint4*)src, (uint4*)dst, N, K);
+    k_pack_weights<<<(unsigned)((total + 255) / 256), 256, 0, st>>>((const uint4*)src, (uint4*)dst, N, K, gate_rows);
 }
 
 // ------------------------------------------------------------------------
@@ -93,11 +98,11 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s
 template <int WN, int WK, int R, int MT, int EPI, int NCH, int DBG = 0, int DW = 4, int PX = 4, int KSTEPS = 2>
 __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, const uint4* Wp, void* outv, int M, int N,
                                                            int K, int ldx, int k_len, size_t split_stride,
-                                                           int up_tile_off, int mask_id, int n_tiles_out) {
+                                                           int mask_id, int n_tiles_out) {
     constexpr int T = WN * WK * 64, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
     constexpr int NST = 3;                              // LDS stages
     static_assert(DW >= 2 && DW <= 6 && PX >= 3 && PX <= 4, "ring depths");
-    static_assert(EPI != EPI_SWIGLU || R == 2 || WN % 2 == 0, "SwiGLU pairs gate and up tiles");
+    static_assert(EPI != EPI_SWIGLU || (WK == 2 && R == 1), "the SwiGLU epilogue is written for two k-slice waves");
     constexpr int XSEG = ROWS * (KC / 8);               // 16-byte segments per X chunk
     constexpr int XPT = (XSEG + T - 1) / T;             // per thread
     constexpr int SPARE = NST * ROWS * LDW;             // LDS element offset of the per-thread spare slots
@@ -118,26 +123,14 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
     const int kbeg = bz * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
     const int KS = K >> 4, NT = N >> 5;
 
-    // n-tiles of this wave.  SwiGLU pairs the gate tile of 32 channels with their up tile
-    // (tile index + up_tile_off): in one wave when R == 2, in an even/odd wave pair when R == 1.
+    // n-tiles of this wave (tiles past the end are clamped and never stored)
     int nt[R];
     bool nt_ok[R];
-    if (EPI == EPI_SWIGLU) {
-        const int ch = R == 2 ? bx * WN + wn : bx * (WN / 2) + (wn >> 1);
-        const bool ok = ch < up_tile_off;
-        const int chc = ok ? ch : up_tile_off - 1;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            nt_ok[r] = ok;
-            nt[r] = chc + ((R == 2 ? r == 1 : (wn & 1)) ? up_tile_off : 0);
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            nt[r] = (bx * WN + wn) * R + r;
-            nt_ok[r] = nt[r] < NT;
-            if (!nt_ok[r]) nt[r] = NT - 1;
-        }
+    for (int r = 0; r < R; ++r) {
+        nt[r] = (bx * WN + wn) * R + r;
+        nt_ok[r] = nt[r] < NT;
+        if (!nt_ok[r]) nt[r] = NT - 1;
     }
     const uint4* wbase[R];
 #pragma unroll
@@ -328,51 +321,45 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
         return;
     }
     if constexpr (WK == 2 && R == 1 && EPI == EPI_SWIGLU) {
-        // The four waves of a channel tile (gate / up x two k-slices) share the output: wave
-        // q = (up ? 1 : 0) + 2 wk finishes group g = q of every row tile and receives the other three
-        // waves' values of that group through LDS.  gate = k-slice 0 + k-slice 1, likewise up.
-        float4* ex = (float4*)smem_u4;                  // [WN/2][receiver][3 senders][MT][64]
-        const int pr = wn >> 1, q = (wn & 1) + 2 * wk;
-        static_for<0, 4>([&](auto iq) {
-            constexpr int me = decltype(iq)::value;
-            if (q == me) {
-                static_for<0, 4>([&](auto ig) {
-                    constexpr int g = decltype(ig)::value;          // receiver
-                    if constexpr (g != me) {
-                        constexpr int slot = me < g ? me : me - 1;
+        // A tile holds 16 channels: rows 0..15 gate, rows 16..31 up, so groups g and g + 2 of a lane are
+        // gate and up of the same four channels.  Wave wk finishes g = wk and receives the other
+        // k-slice's values of groups wk and wk + 2 through LDS (k-slice 0 plus k-slice 1).
+        float4* ex = (float4*)smem_u4;                  // [WN][sender wk][MT][gate, up][64]
+        static_for<0, 2>([&](auto iw) {
+            constexpr int w = decltype(iw)::value;
+            if (wk == w) {
 #pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            ex[(((pr * 4 + g) * 3 + slot) * MT + mt) * 64 + lane] =
-                                make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        constexpr int gother = 1 - w;
+                        const int g = gother + 2 * h;
+                        ex[(((wn * 2 + w) * MT + mt) * 2 + h) * 64 + lane] =
+                            make_float4(acc[0][mt][g * 4], acc[0][mt][g * 4 + 1], acc[0][mt][g * 4 + 2], acc[0][mt][g * 4 + 3]);
                     }
-                });
             }
         });
         __syncthreads();
         bf16_t* out = (bf16_t*)outv;
-        const int ch = bx * (WN / 2) + pr;
-        static_for<0, 4>([&](auto iq) {
-            constexpr int me = decltype(iq)::value;
-            if (q == me && ch < up_tile_off) {
+        const int F = N >> 1;                           // output channels = row stride of the output
+        static_for<0, 2>([&](auto iw) {
+            constexpr int w = decltype(iw)::value;
+            if (wk == w && nt_ok[0]) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    float4 v[4];                                    // by sender: gate k0, up k0, gate k1, up k1
-                    static_for<0, 4>([&](auto is) {
-                        constexpr int sd = decltype(is)::value;
-                        if constexpr (sd == me)
-                            v[sd] = make_float4(acc[0][mt][me * 4], acc[0][mt][me * 4 + 1], acc[0][mt][me * 4 + 2], acc[0][mt][me * 4 + 3]);
-                        else
-                            v[sd] = ex[(((pr * 4 + me) * 3 + (sd < me ? sd : sd - 1)) * MT + mt) * 64 + lane];
-                    });
-                    const float gv[4] = {v[0].x + v[2].x, v[0].y + v[2].y, v[0].z + v[2].z, v[0].w + v[2].w};
-                    const float uv[4] = {v[1].x + v[3].x, v[1].y + v[3].y, v[1].z + v[3].z, v[1].w + v[3].w};
+                    const float4 og = ex[(((wn * 2 + (1 - w)) * MT + mt) * 2 + 0) * 64 + lane];
+                    const float4 ou = ex[(((wn * 2 + (1 - w)) * MT + mt) * 2 + 1) * 64 + lane];
+                    const float gv[4] = {acc[0][mt][w * 4] + og.x, acc[0][mt][w * 4 + 1] + og.y,
+                                         acc[0][mt][w * 4 + 2] + og.z, acc[0][mt][w * 4 + 3] + og.w};
+                    const float uv[4] = {acc[0][mt][(w + 2) * 4] + ou.x, acc[0][mt][(w + 2) * 4 + 1] + ou.y,
+                                         acc[0][mt][(w + 2) * 4 + 2] + ou.z, acc[0][mt][(w + 2) * 4 + 3] + ou.w};
                     uint16_t o[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) o[j] = f2bf_m(gv[j] / (1.0f + expf(-gv[j])) * uv[j]);
                     const int m = m0 + mt * 32 + lm;
-                    const int f = ch * 32 + me * 8 + lh * 4;
+                    const int f = nt[0] * 16 + w * 8 + lh * 4;
                     if (m < M)
-                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
+                        *(uint2*)(out + (size_t)m * F + f) =
                             make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
                 }
             }
@@ -427,62 +414,6 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
                 }
             }
         }
-    } else if (EPI == EPI_SWIGLU) {
-        bf16_t* out = (bf16_t*)outv;
-        if constexpr (R == 2) {
-            // gate (r = 0) and up (r = 1) of the same channels sit in the same lane
-            if (lead && nt_ok[0]) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const int m = m0 + mt * 32 + lm;
-                    if (m >= M) continue;
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int f = nt[0] * 32 + g * 8 + lh * 4;
-                        uint16_t o[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float gv = acc[0][mt][g * 4 + j], uv = acc[R - 1][mt][g * 4 + j];
-                            o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
-                        }
-                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
-                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                    }
-                }
-            }
-        } else {
-            // the up wave hands its tile to the gate wave of the same channels through LDS
-            float* xch = (float*)smem_u4;               // [WN/2][MT*16][64]
-            if (WK > 1) __syncthreads();                // the k-slice reduction has finished reading
-            if (lead && (wn & 1)) {
-                float* dst = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) dst[(mt * 16 + i) * 64] = acc[0][mt][i];
-            }
-            __syncthreads();
-            if (lead && !(wn & 1) && nt_ok[0]) {
-                const float* src = xch + ((size_t)(wn >> 1) * MT * 16) * 64 + lane;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const int m = m0 + mt * 32 + lm;
-                    if (m >= M) continue;
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int f = nt[0] * 32 + g * 8 + lh * 4;
-                        uint16_t o[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float gv = acc[0][mt][g * 4 + j], uv = src[(mt * 16 + g * 4 + j) * 64];
-                            o[j] = f2bf_m(gv / (1.0f + expf(-gv)) * uv);
-                        }
-                        *(uint2*)(out + (size_t)m * (up_tile_off * 32) + f) =
-                            make_uint2((uint32_t)o[0] | ((uint32_t)o[1] << 16), (uint32_t)o[2] | ((uint32_t)o[3] << 16));
-                    }
-                }
-            }
-        }
     } else if (lead) {
         // LM head: per (row, n-tile) partial over the tile's 32 vocabulary rows
         float* out = (float*)outv;
@@ -528,12 +459,11 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 // ------------------------------------------------------------------------
 template <int WN, int WK, int R, int MT, int EPI, int NCH>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
-                       int up_tile_off, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
+                       int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
     constexpr int KC = WK * 32, ROWS = MT * 32, LDW = KC + 8;
     constexpr size_t xbytes = (size_t)3 * ROWS * LDW * 2 + (size_t)WN * WK * 64 * 16;   // three stages + spare slots
     // epilogue exchange areas: see the kernel's epilogues
-    constexpr size_t rbytes = (WK == 2 && R == 1 && EPI == EPI_F32)      ? (size_t)WN * 2 * MT * 2 * 1024
-                              : (WK == 2 && R == 1 && EPI == EPI_SWIGLU) ? (size_t)(WN / 2) * 12 * MT * 1024
+    constexpr size_t rbytes = (WK == 2 && R == 1 && EPI != EPI_LMHEAD) ? (size_t)WN * 2 * MT * 2 * 1024
                               : WK > 1 ? (size_t)(WK - 1) * WN * R * MT * 16 * 64 * 4
                                        : (size_t)(WN / 2 + 1) * MT * 16 * 64 * 4;
     constexpr size_t smem = xbytes > rbytes ? xbytes : rbytes;
@@ -545,11 +475,10 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
             return false;
         attr_done = true;
     }
-    const int tiles = EPI == EPI_SWIGLU ? up_tile_off : N / 32;
-    const int per_wg = EPI == EPI_SWIGLU ? (R == 2 ? WN : WN / 2) : WN * R;
+    const int tiles = N / 32, per_wg = WN * R;
     dim3 grid((tiles + per_wg - 1) / per_wg, m_chunks, split);
     hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K, K / split, split_stride,
-                       up_tile_off, mask_id, n_tiles_out);
+                       mask_id, n_tiles_out);
     return true;
 }
 
@@ -557,11 +486,11 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
 // other row counts round up (padding rows are zero and never stored).
 template <int WN, int WK, int R, int EPI, int NCH>
 static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
-                      size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
+                      size_t split_stride, int mask_id, int n_tiles_out, int m_chunks,
                       hipStream_t st) {
 #define SSD_MT_CASE(v)                                                                                          \
     case v:                                                                                                     \
-        return launch_one<WN, WK, R, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,  \
+        return launch_one<WN, WK, R, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, mask_id,  \
                                                n_tiles_out, m_chunks, st);
     switch (mt) {
         SSD_MT_CASE(1)
@@ -575,11 +504,11 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
 // Chunk counts with a straight-line kernel; anything else takes the looped one (NCH = 0).
 template <int WN, int WK, int R, int EPI>
 static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
-                       size_t split_stride, int up_tile_off, int mask_id, int n_tiles_out, int m_chunks,
+                       size_t split_stride, int mask_id, int n_tiles_out, int m_chunks,
                        hipStream_t st) {
 #define SSD_NCH_CASE(v)                                                                                           \
     case v:                                                                                                       \
-        return launch_mt<WN, WK, R, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id,      \
+        return launch_mt<WN, WK, R, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id,      \
                                          n_tiles_out, m_chunks, st);
     if (EPI == EPI_F32) {
         switch (nch) {
@@ -593,7 +522,7 @@ static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* 
         switch (nch) { SSD_NCH_CASE(64) }
     }
 #undef SSD_NCH_CASE
-    return launch_mt<WN, WK, R, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, up_tile_off, mask_id, n_tiles_out,
+    return launch_mt<WN, WK, R, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out,
                                      m_chunks, st);
 }
 
@@ -620,15 +549,17 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
     const uint4* wp = (const uint4*)W.packed;
     const size_t stride = (size_t)c->dm.max_rows * (size_t)c->part_cols;
     if (epi == EPI_SWIGLU) {
-        // W = [2F, d]: gate rows then up rows; the kernel's N is F
-        const int F = N / 2;
-        if (F % 32) return false;
+        // W = [2F, d] packed with gate and up rows interleaved per 16 channels: N/32 tiles of 16
+        // channels each, any number of them per work-group; 96-row n-blocks give the 8B shape
+        // (768 tiles) exactly one work-group per CU
         *n_split = 1;
-        return launch_nch<WN, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, F, K, 1, 0, F / 32, -1, 0, m_chunks, st);
+        if ((N / 32) % 3 == 0)
+            return launch_nch<3, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, N, K, 1, 0, -1, 0, m_chunks, st);
+        return launch_nch<WN, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, N, K, 1, 0, -1, 0, m_chunks, st);
     }
     if (epi == EPI_LMHEAD) {
         *n_split = lm_tiles_mfma(N);
-        return launch_nch<WN, WK, 1, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, 0, c->dm.mask_id, N / 32, m_chunks, st);
+        return launch_nch<WN, WK, 1, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, c->dm.mask_id, N / 32, m_chunks, st);
     }
     // Work-group shape and split along K: functions of the weight shape alone, chosen so that the
     // grid comes close to one work-group per CU (256) with at least 16 K chunks each where the
@@ -650,9 +581,9 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
     const int split = pick_split(K, KC, want);
     *n_split = split;
     const int nch = K / split / KC;
-    if (wn == 3) return launch_nch<3, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
-    if (wn == 2) return launch_nch<2, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
-    return launch_nch<WN, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, 0, -1, 0, m_chunks, st);
+    if (wn == 3) return launch_nch<3, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
+    if (wn == 2) return launch_nch<2, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
+    return launch_nch<WN, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
 }
 #endif
 

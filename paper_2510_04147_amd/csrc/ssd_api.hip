@@ -168,18 +168,18 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     // weights: keep the caller's pointers, and repack what tiles into MFMA fragment order
     {
         char* pk = (char*)c->b.packed;
-        auto mk = [&](const void* raw, int N, int K) {
+        auto mk = [&](const void* raw, int N, int K, int gate_rows = 0) {
             Wt t{raw, nullptr, N, K};
             if (packable(d, N, K)) {
                 t.packed = pk;
-                launch_pack_weights(raw, pk, N, K, c->stream);
+                launch_pack_weights(raw, pk, N, K, gate_rows, c->stream);
                 pk += ((size_t)N * K * 2 + 255) & ~(size_t)255;
             }
             return t;
         };
         c->lw.resize(d.L);
         for (int l = 0; l < d.L; ++l)
-            c->lw[l] = LayerW{mk(w->wqkv[l], d.nqkv(), d.d), mk(w->wo[l], d.d, d.nq()), mk(w->wgu[l], 2 * d.F, d.d),
+            c->lw[l] = LayerW{mk(w->wqkv[l], d.nqkv(), d.d), mk(w->wo[l], d.d, d.nq()), mk(w->wgu[l], 2 * d.F, d.d, d.F),
                               mk(w->wdown[l], d.d, d.F), w->norm1[l], w->norm2[l]};
         c->lm_head = mk(w->lm_head, d.V, d.d);
     }

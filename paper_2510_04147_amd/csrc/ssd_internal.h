@@ -187,7 +187,8 @@ struct ssd_ctx {
 void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes);
 void launch_embed(const ssd_ctx* c, int M, hipStream_t st);
 void launch_norm(const ssd_ctx* c, int M, const float* gain, int n_part, hipStream_t st);
-void launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t st);
+// gate_rows > 0: the matrix is gate rows then up rows; interleave them per 16 channels
+void launch_pack_weights(const void* src, void* dst, int N, int K, int gate_rows, hipStream_t st);
 void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st);
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
 void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st);

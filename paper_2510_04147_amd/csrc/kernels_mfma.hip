@@ -26,6 +26,7 @@
 
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Compile-time loop: f(integral_constant<int, C>) for C in [BEGIN, END).  The ring slots of the
@@ -92,7 +93,8 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, int gate_rows
 // spreads the grid's weight streams over the HBM channels; the order depends
 // on the n-tile only, so a row's summation order is the same in every forward.
 // DBG is for measurement builds only (bit 0: no MFMA, bit 1: no activation
-// loads, bit 2: no epilogue, bit 3: every chunk reads chunk 0's activations); the library
+// loads, bit 2: no epilogue, bit 3: every chunk reads chunk 0's activations, bit 4: no weight
+// loads, bit 5: weight loads with the default cache policy); the library
 // instantiates DBG = 0.
 // ------------------------------------------------------------------------
 template <int WN, int WK, int R, int MT, int EPI, int NCH, int DBG = 0, int DW = 4, int PX = 4, int KSTEPS = 2>
@@ -176,7 +178,18 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks) dst[r * KSTEPS + ks] = wbase[r][off + ks * 64];
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                if (DBG & 16)
+                    dst[r * KSTEPS + ks] = make_uint4((unsigned)off, (unsigned)ks, 0u, 0u);
+                else if (DBG & 32)
+                    dst[r * KSTEPS + ks] = wbase[r][off + ks * 64];
+                else {
+                    // weights are read once per launch: a non-temporal load keeps them from evicting the
+                    // activations, which every work-group of the XCD re-reads, from L2
+                    const u32x4 v = __builtin_nontemporal_load((const u32x4*)&wbase[r][off + ks * 64]);
+                    dst[r * KSTEPS + ks] = make_uint4(v.x, v.y, v.z, v.w);
+                }
+            }
     };
     auto issue_x = [&](uint4* dst, int c) {
         const size_t off = (DBG & 8) ? (size_t)0 : (size_t)chunk_at(c) * KC;

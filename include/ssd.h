@@ -189,7 +189,10 @@ int ssd_generate(ssd_ctx* ctx, int n, const int32_t* const* prompts, const int* 
                  int gen_len, int block, int draft_depth, int32_t* out_tokens, ssd_stats* stats);
 
 /* Kernel selection: 0 = plain FMA kernels (any dtype), 1 = MFMA kernels where
- * available (bf16).  Default 1.  Returns the previous value or an error. */
+ * available (bf16), the rotary stage fused into the attention kernel where the
+ * forward's shape allows, 2 = as 1 with the rotary stage always a kernel of
+ * its own (same results; for measurement).  Default 1.  Returns the previous
+ * value or an error. */
 int ssd_set_kernel_path(ssd_ctx* ctx, int path);
 
 /* Block-boundary fusion in ssd_generate (Section 3.1: blocks are decoded in

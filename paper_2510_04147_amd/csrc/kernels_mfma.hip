@@ -621,7 +621,11 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 #define ATTN_WAVES 8   // waves per (node, head, query tile): wave w takes key tiles w, w+8, ...
 
-template <int DH>
+// FUSED: the kernel starts from the QKV projection's fp32 partial sums instead of ready q / k / v: it
+// adds the partial sums in split order, applies the rotary embedding to its head's queries and to
+// the node's own keys and keeps the own key / value tile in LDS in fragment order.  For forwards whose
+// nodes have at most 32 rows (one query tile) and append nothing to the cache, head size 128.
+template <int DH, bool FUSED>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* __restrict__ fw,
                                                                const bf16_t* __restrict__ q,
                                                                const bf16_t* __restrict__ kown,
@@ -629,13 +633,20 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
                                                                const bf16_t* __restrict__ kcache,
                                                                const bf16_t* __restrict__ vcache,
                                                                bf16_t* __restrict__ out, int Hq, int Hkv, int layer,
-                                                               int max_seqs, int seq_stride, int vt_rows, float scale) {
+                                                               int max_seqs, int seq_stride, int vt_rows, float scale,
+                                                               const float* __restrict__ part, int n_part,
+                                                               size_t part_stride, const float* __restrict__ cosT,
+                                                               const float* __restrict__ sinT) {
     constexpr int KST = DH / 16, DT = DH / 32;
     constexpr int NE = DT * 16;                                      // O^T values per lane
     constexpr int EPW = NE / ATTN_WAVES;                             // of which each wave merges EPW
     static_assert(EPW % 4 == 0, "the merge writes groups of four head channels");
+    static_assert(!FUSED || DH == 128, "the fused rotary stage is laid out for head size 128");
     __shared__ float mrg[ATTN_WAVES][NE + 2][64];                    // every wave's partial (O^T, max, sum)
     __shared__ __attribute__((aligned(16))) bf16_t qs[32][DH + 8];   // the query tile, shared by the waves
+    // FUSED: the node's own key and value tile, fragment order, in the (not yet used) merge area
+    bf16_t* ks_own = (bf16_t*)&mrg[0][0][0];
+    bf16_t* vs_own = ks_own + 32 * DH;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lm = lane & 31, lh = lane >> 5;
     // Work-groups go to the 8 XCDs round-robin by their linear id, and every XCD has an L2 of its
@@ -680,31 +691,102 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     const int pre_tiles = (nd.S + 31) >> 5, n_tiles = pre_tiles + ((nd.blen + 31) >> 5);
     // positions past the end of the prefix or of the node hold stale memory: masked (keys) or zeroed (values)
     auto load_k = [&](bf16x8(&kf)[KST], int t) {
-        const bf16_t* kp = (t >= pre_tiles ? ko + (size_t)(t - pre_tiles) * 32 * DH : kc + (size_t)t * 32 * DH) + lane * 8;
+        const bf16_t* kp;
+        if (t >= pre_tiles)
+            kp = (FUSED ? ks_own : ko + (size_t)(t - pre_tiles) * 32 * DH) + lane * 8;
+        else
+            kp = kc + (size_t)t * 32 * DH + lane * 8;
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks) kf[ks] = *(const bf16x8*)(kp + ks * 512);
     };
     auto load_v = [&](bf16x8(&vf)[DT][2], int t) {
-        const bf16_t* vp = (t >= pre_tiles ? vo + (size_t)(t - pre_tiles) * 32 * DH : vc + (size_t)t * 32 * DH) + lane * 8;
+        const bf16_t* vp;
+        if (t >= pre_tiles)
+            vp = (FUSED ? vs_own : vo + (size_t)(t - pre_tiles) * 32 * DH) + lane * 8;
+        else
+            vp = vc + (size_t)t * 32 * DH + lane * 8;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int st = 0; st < 2; ++st) vf[dt][st] = *(const bf16x8*)(vp + (dt * 2 + st) * 512);
     };
     bf16x8 kf[KST], kn[KST], vf[DT][2], vn[DT][2];
-    if (wave < n_tiles) {
+    // the first tile's loads go out before anything else (FUSED: unless it is the own tile, which is
+    // not in LDS yet)
+    const bool first_later = FUSED && wave >= pre_tiles;
+    if (wave < n_tiles && !first_later) {
         load_k(kf, wave);
         load_v(vf, wave);
     }
-    // the query tile, after the first key/value loads are on their way; rows past the end of the
-    // block are read from row 0 and never written back
-    for (int idx = threadIdx.x; idx < 32 * (DH / 8); idx += ATTN_WAVES * 64) {
-        const int r = idx / (DH / 8), c8 = idx % (DH / 8);
-        const int rin = qt * 32 + r;
-        const int grow = nd.row0 + (rin < nd.blen ? rin : 0);
-        *(bf16x8*)&qs[r][c8 * 8] = *(const bf16x8*)(q + (size_t)grow * nq + head * DH + c8 * 8);
+    if constexpr (FUSED) {
+        // 32 rows x 16 column groups.  q and k: thread (r, cg) owns channels [4cg, 4cg+4) of both rotary
+        // halves; v: channels [8cg, 8cg+8).  Rows past the end of the block take row 0's values
+        // (queries: never written back; keys: masked) or zeros (values).
+        constexpr int HALF = DH / 2;
+        const int tid = threadIdx.x, r = tid >> 4, cg = tid & 15;
+        const bool rvalid = r < nd.blen;
+        const int row = nd.row0 + (rvalid ? r : 0), pos = nd.S + (rvalid ? r : 0);
+        const int nkv = Hkv * DH, nqkv = nq + 2 * nkv;
+        const float* src = part + (size_t)row * nqkv;
+        auto load4 = [&](int col, float* dst) {             // 4 values from column col, partial sums in split order
+            float4 a = *(const float4*)(src + col);
+            for (int sp = 1; sp < n_part; ++sp) {
+                const float4 b = *(const float4*)(src + sp * part_stride + col);
+                a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+            }
+            dst[0] = a.x; dst[1] = a.y; dst[2] = a.z; dst[3] = a.w;
+        };
+        const int i0 = cg * 4;
+        float qa[4], qb[4], ka[4], kb[4], vv[8], cs[4], sn[4];
+        load4(head * DH + i0, qa);
+        load4(head * DH + HALF + i0, qb);
+        load4(nq + kvh * DH + i0, ka);
+        load4(nq + kvh * DH + HALF + i0, kb);
+        load4(nq + nkv + kvh * DH + cg * 8, vv);
+        load4(nq + nkv + kvh * DH + cg * 8 + 4, vv + 4);
+        {
+            const float4 c4 = *(const float4*)(cosT + (size_t)pos * HALF + i0), s4 = *(const float4*)(sinT + (size_t)pos * HALF + i0);
+            cs[0] = c4.x; cs[1] = c4.y; cs[2] = c4.z; cs[3] = c4.w;
+            sn[0] = s4.x; sn[1] = s4.y; sn[2] = s4.z; sn[3] = s4.w;
+        }
+        uint16_t q1[4], q2[4], k1[4], k2[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float o1, o2;
+            rope_pair(qa[j], qb[j], cs[j], sn[j], o1, o2);
+            q1[j] = f2bf_m(o1); q2[j] = f2bf_m(o2);
+            rope_pair(ka[j], kb[j], cs[j], sn[j], o1, o2);
+            k1[j] = f2bf_m(o1); k2[j] = f2bf_m(o2);
+        }
+        auto pack4 = [](const uint16_t* h) {
+            return make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+        };
+        *(uint2*)&qs[r][i0] = pack4(q1);
+        *(uint2*)&qs[r][HALF + i0] = pack4(q2);
+        // four consecutive channels starting at a multiple of four stay contiguous in fragment order
+        *(uint2*)&ks_own[kfrag_off(r, i0, DH)] = pack4(k1);
+        *(uint2*)&ks_own[kfrag_off(r, HALF + i0, DH)] = pack4(k2);
+        uint16_t vb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            vb[j] = rvalid ? f2bf_m(vv[j]) : (uint16_t)0;
+            vs_own[vfrag_off(r, cg * 8 + j, DH)] = vb[j];             // scattered 2-byte LDS stores, 8 per thread
+        }
+    } else {
+        // the query tile, after the first key/value loads are on their way; rows past the end of the
+        // block are read from row 0 and never written back
+        for (int idx = threadIdx.x; idx < 32 * (DH / 8); idx += ATTN_WAVES * 64) {
+            const int r = idx / (DH / 8), c8 = idx % (DH / 8);
+            const int rin = qt * 32 + r;
+            const int grow = nd.row0 + (rin < nd.blen ? rin : 0);
+            *(bf16x8*)&qs[r][c8 * 8] = *(const bf16x8*)(q + (size_t)grow * nq + head * DH + c8 * 8);
+        }
     }
-    __syncthreads();                                                // the query tile is in LDS
+    __syncthreads();                                                // the query tile (FUSED: and the own tile) is in LDS
+    if (wave < n_tiles && first_later) {
+        load_k(kf, wave);
+        load_v(vf, wave);
+    }
     for (int t = wave; t < n_tiles; t += ATTN_WAVES) {
         const bool own = t >= pre_tiles;
         const int t0 = (own ? t - pre_tiles : t) * 32;              // first key of the tile, in its own index space
@@ -773,6 +855,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     }
     // ---- merge the waves' partial results: every wave publishes its partial, then wave w folds
     // values [w*EPW, (w+1)*EPW) of all waves in wave order (fixed, independent of the forward's shape)
+    if constexpr (FUSED) __syncthreads();                           // the own tile shared the merge area
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -815,17 +898,26 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     }
 }
 
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hipStream_t st) {
+bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen) {
+    return c->dm.dtype == SSD_BF16 && c->dm.dh == 128 && max_blen <= 32;
+}
+
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st) {
     const Dims& d = c->dm;
     dim3 grid(n_nodes * d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
+    const size_t ps = (size_t)d.max_rows * c->part_cols;
 #define SSD_ATTN_ARGS                                                                                                  \
     c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown, (const bf16_t*)c->b.kcache, \
-        (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale
-    if (d.dh == 128)
-        k_attn_mfma<128><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+        (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale, \
+        c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin
+    if (n_part >= 0) {
+        if (!attn_mfma_can_fuse_rope(c, max_blen)) return false;
+        k_attn_mfma<128, true><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+    } else if (d.dh == 128)
+        k_attn_mfma<128, false><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
     else if (d.dh == 64)
-        k_attn_mfma<64><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+        k_attn_mfma<64, false><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
     else
         return false;
 #undef SSD_ATTN_ARGS

@@ -197,8 +197,7 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
 #pragma unroll
         for (int j = 0; j < PT; ++j) {
             const float c = cosT[(size_t)pos * HALF + i0 + j], sn = sinT[(size_t)pos * HALF + i0 + j];
-            o1[j] = x1[j] * c - x2[j] * sn;
-            o2[j] = x2[j] * c + x1[j] * sn;
+            rope_pair(x1[j], x2[j], c, sn, o1[j], o2[j]);
         }
         if (rvalid) {
             if (hh < Hq) {

@@ -260,7 +260,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_cached_len(ssd_ctx* c,
 }
 
 extern "C" __attribute__((visibility("default"))) int ssd_set_kernel_path(ssd_ctx* c, int path) {
-    if (!c || (path != 0 && path != 1)) return SSD_EINVAL;
+    if (!c || path < 0 || path > 2) return SSD_EINVAL;
     const int old = c->kernel_path;
     c->kernel_path = path;
     return old;
@@ -361,7 +361,7 @@ struct Upload {           // block state to push before the forward (stateless A
 static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void* out, int M, int* n_split) {
     ProfScope ps(c, cls);
     *n_split = 1;
-    if (c->kernel_path == 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, n_split, c->stream))
+    if (c->kernel_path >= 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, n_split, c->stream))
         return;
     const int N = epi == EPI_SWIGLU ? W.N / 2 : W.N;
     *n_split = epi == EPI_LMHEAD ? lm_tiles_plain(N) : 1;
@@ -399,7 +399,11 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
 
     const int M = hd.M, ML = hd.M_logits;
     int max_blen = 0;
-    for (int i = 0; i < hd.n_nodes; ++i) max_blen = std::max(max_blen, hd.nodes[i].blen);
+    bool any_write_kv = false;
+    for (int i = 0; i < hd.n_nodes; ++i) {
+        max_blen = std::max(max_blen, hd.nodes[i].blen);
+        any_write_kv |= hd.nodes[i].write_kv != 0;
+    }
 
     // ---- the kernel sequence: a function of (M, ML, n_nodes, n_groups, max_blen, kernel path) only
     auto launch_all = [&]() {
@@ -414,11 +418,19 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
             { ProfScope ps(c, KC_NORM); launch_norm(c, M, w.norm1, n_part, st); }
             n_part = 0;
             gemm(c, KC_GEMM_QKV, EPI_F32, c->b.xn, w.wqkv, c->b.part, M, &ns);
-            { ProfScope ps(c, KC_ROPE); launch_rope(c, hd.n_nodes, max_blen, l, ns, st); }
-            if (l == d.L - 1 && ML == 0) break;      // a pure KV pass needs nothing after the last layer's K and V
+            // blocks of at most 32 rows: the attention kernel sums the partial sums and applies the
+            // rotary embedding itself; a pure KV pass needs only the last layer's K and V, not its attention
+            const bool last_kv_only = l == d.L - 1 && ML == 0;
+            // (not in a forward that appends KV: with block-boundary fusion the next block's node reads
+            // those cache entries in the same layer, so they must be written by an earlier kernel)
+            const bool fused = c->kernel_path == 1 && !last_kv_only && !any_write_kv &&
+                               attn_mfma_can_fuse_rope(c, max_blen);
+            if (!fused) { ProfScope ps(c, KC_ROPE); launch_rope(c, hd.n_nodes, max_blen, l, ns, st); }
+            if (last_kv_only) break;
             {
                 ProfScope ps(c, KC_ATTN);
-                if (!(c->kernel_path == 1 && d.dtype == SSD_BF16 && launch_attn_mfma(c, hd.n_nodes, max_blen, l, st)))
+                if (!(c->kernel_path >= 1 && d.dtype == SSD_BF16 &&
+                      launch_attn_mfma(c, hd.n_nodes, max_blen, l, fused ? ns : -1, st)))
                     launch_attn_plain(c, M, l, st);
             }
             gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);

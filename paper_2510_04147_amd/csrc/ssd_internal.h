@@ -90,6 +90,13 @@ struct Dims {
 //           (fragment of O^T = V^T P^T: lane (c%32, half) holds the 8 keys whose probabilities
 //           the same lane half holds after the S^T product).
 // A head's region of n positions (n a multiple of 32) holds n*dh elements in either order.
+// Rotary embedding of one (x1, x2) = (channel i, channel i + dh/2) pair, with the roundings spelled
+// out so that every kernel that applies it produces the same bits.
+__device__ __forceinline__ void rope_pair(float x1, float x2, float c, float sn, float& o1, float& o2) {
+    o1 = __fmaf_rn(x1, c, -__fmul_rn(x2, sn));
+    o2 = __fmaf_rn(x2, c, __fmul_rn(x1, sn));
+}
+
 __host__ __device__ inline size_t kfrag_off(int p, int c, int dh) {
     return ((((size_t)(p >> 5) * (dh >> 4) + (c >> 4)) * 64 + ((c >> 3) & 1) * 32 + (p & 31)) << 3) + (c & 7);
 }
@@ -207,4 +214,7 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
 bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, void* out, int M, int* n_split,
                       hipStream_t st);
 int lm_tiles_mfma(int V);
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, hipStream_t st);
+// n_part >= 0: the kernel also sums the QKV projection's n_part partial sums and applies the rotary
+// embedding itself (nodes of at most 32 rows, head size 128, no cache append); n_part < 0: q / kown / vown are ready
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st);
+bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen);

@@ -11,6 +11,13 @@
                predictions as the next drafts.
   bruteforce   stepwise decoding with no cache: the whole sequence is
                recomputed under the block-causal mask for every token.
+  mix order    ssd(..., mix_order=True): the greedy chain plus one extra node per
+               non-leaf chain node that skips the next draft (Section 5.2,
+               Table 3): when node m's stepwise choice is draft m+2 instead of
+               draft m+1 (same candidates, different order), that draft is
+               accepted and the extra node, which holds drafts 1..m and m+2,
+               supplies one more token.  Extra nodes have no children: 2N nodes
+               for N drafts (the table's batch sizes 6 / 8 / 10).
 
 Readings where the paper is silent (all also applied by the HIP path):
   * confidence c = softmax probability of the arg-max token (Section 3.2.2);
@@ -79,6 +86,47 @@ def build_chain(tok, masked, drafts):
         t[q], mk[q] = d, False
         nodes.append((list(t), list(mk)))
     return nodes
+
+
+def build_mix_order(tok, masked, drafts):
+    """Nodes of the mix-order tree (Section 5.2): the len(drafts)+1 chain nodes, then for
+    m = 0 .. len(drafts)-2 the node with drafts 1..m and draft m+2 written in."""
+    nodes = build_chain(tok, masked, drafts)
+    for m in range(len(drafts) - 1):
+        t, mk = list(tok), list(masked)
+        for (q, d) in list(drafts[:m]) + [drafts[m + 1]]:
+            assert mk[q], "a draft position must still be masked"
+            t[q], mk[q] = d, False
+        nodes.append((t, mk))
+    return nodes
+
+
+def accept_mix_order(node_t, node_c, node_masked, drafts, n_draft_next):
+    """Traversal of the mix-order tree.  Nodes are ordered as build_mix_order returns them.
+    As accept_chain, except that a mismatch at chain node m whose stepwise choice equals draft
+    m+2 accepts that draft and continues at the extra node of m, whose own choice is accepted
+    as the last token.  Returns (accepted, next_drafts, index of the node the walk ended at)."""
+    n = len(drafts)
+    m = 0
+    while True:
+        p = stepwise_choice(node_c[m], node_masked[m])
+        t = int(node_t[m][p])
+        if m < n and (p, t) == (drafts[m][0], int(drafts[m][1])):
+            m += 1
+            continue
+        break
+    accepted = [(q, int(d)) for (q, d) in drafts[:m]]
+    last = m
+    if m + 1 < n and (p, t) == (drafts[m + 1][0], int(drafts[m + 1][1])):
+        accepted.append((p, t))                      # the out-of-order draft
+        last = n + 1 + m                             # its extra node
+        p = stepwise_choice(node_c[last], node_masked[last])
+        t = int(node_t[last][p])
+    accepted.append((p, t))
+    rest = rank_positions(node_c[last], node_masked[last], exclude=p)
+    n_next = min(n_draft_next, max(len(rest) - 1, 0))
+    next_drafts = [(q, int(node_t[last][q])) for q in rest[:n_next]]
+    return accepted, next_drafts, last
 
 
 def accept_chain(node_t, node_c, node_masked, drafts, n_draft_next):
@@ -150,11 +198,12 @@ def stepwise(w, cfg, prompt, gen_len, block, dtype=torch.float64, trace=None, ma
 
 
 def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None, max_blocks=None,
-        max_forwards=None):
+        max_forwards=None, mix_order=False):
     """Self Speculative Decoding with draft length n_draft (Algorithm 1).
     Returns (tokens, stats) with stats['accept_hist'][a] = number of forwards
     that accepted a tokens.  max_blocks / max_forwards stop early (the tokens
-    returned are then a prefix; used to sample forwards of large models)."""
+    returned are then a prefix; used to sample forwards of large models).
+    mix_order: verify the mix-order tree instead of the greedy chain (Section 5.2)."""
     P = len(prompt)
     cache = _prefill(w, cfg, prompt, dtype)
     out, forwards, kv_passes = [], 0, 1
@@ -168,11 +217,11 @@ def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None
         while any(masked):
             if max_forwards is not None and forwards >= max_forwards:
                 return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
-            nodes = build_chain(tok, masked, drafts)
+            nodes = build_mix_order(tok, masked, drafts) if mix_order else build_chain(tok, masked, drafts)
             # one batched forward over all nodes (Eq. 5); nodes do not see each other
             preds = [_node_forward(w, cfg, nt, S, cache, dtype) for (nt, _) in nodes]
             forwards += 1
-            accepted, next_drafts, m = accept_chain(
+            accepted, next_drafts, m = (accept_mix_order if mix_order else accept_chain)(
                 [p[0] for p in preds], [p[2] for p in preds], [nm for (_, nm) in nodes],
                 drafts, n_draft)
             if trace is not None:

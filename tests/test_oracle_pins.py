@@ -294,6 +294,97 @@ def test_accept_chain_ties_and_last_token_of_block():
     assert m == 1 and acc == [(0, 3), (1, 2)] and nxt == []
 
 
+# --------------------------------------------------------------- mix-order tree
+def test_mix_order_tree_shape():
+    """Section 5.2 / Table 3: the N+1 chain nodes plus one node per non-leaf chain node that skips
+    the next draft: 2N nodes (6 / 8 / 10 for N = 3 / 4 / 5); the extra node of m holds drafts
+    1..m and m+2."""
+    tok, masked = [9] * 8, [True] * 8
+    for N, size in ((1, 2), (2, 4), (3, 6), (4, 8), (5, 10)):
+        drafts = [(p, 20 + p) for p in range(N)]
+        nodes = decode.build_mix_order(tok, masked, drafts)
+        assert len(nodes) == size == max(2 * N, N + 1)
+        assert nodes[:N + 1] == decode.build_chain(tok, masked, drafts)
+        for m in range(N - 1):
+            t, mk = nodes[N + 1 + m]
+            placed = [p for p in range(8) if not mk[p]]
+            assert placed == sorted([q for q, _ in drafts[:m]] + [drafts[m + 1][0]])
+            assert all(t[q] == 20 + q for q in placed) and t[drafts[m][0]] == 9
+    assert decode.build_mix_order(tok, masked, []) == decode.build_chain(tok, masked, [])
+
+
+def test_accept_mix_order_by_hand():
+    """Drafts (2,'7'), (0,'8'), (3,'9') on a block of 5 (position 4 decoded).  Node 0 prefers
+    position 0 with token 8 = the second draft: greedy accepts one token, mix order accepts the
+    second draft and the choice of the node that holds it."""
+    drafts = [(2, 7), (0, 8), (3, 9)]
+    root = [True, True, True, True, False]
+    chain = [root]
+    for q, _ in drafts:
+        mk = list(chain[-1]); mk[q] = False; chain.append(mk)
+    extra0 = [False, True, True, True, False]              # draft 2 only
+    extra1 = [True, True, False, False, False]             # draft 1 and draft 3
+    masked = chain + [extra0, extra1]
+    c = [[.9, .2, .8, .3, 0], [.8, .2, 0, .3, 0], [0, .2, 0, .7, 0], [0, .6, 0, 0, 0],
+         [0, .1, .4, .5, 0], [.2, .3, 0, 0, 0]]
+    t = [[8, 5, 7, 9, 0], [8, 5, 0, 9, 0], [0, 5, 0, 9, 0], [0, 6, 0, 0, 0],
+         [0, 5, 7, 4, 0], [1, 2, 0, 0, 0]]
+    cc, tt = _mk(c, t)
+    acc, nxt, last = decode.accept_mix_order(tt, cc, masked, drafts, 3)
+    assert acc == [(0, 8), (3, 4)] and last == 4            # out-of-order draft + its node's choice
+    assert nxt == [(2, 7)]                                  # masked {1, 2} left, the leaf keeps one
+    g_acc, _, g_m = decode.accept_chain(tt[:4], cc[:4], masked[:4], drafts, 3)
+    assert g_acc == [(0, 8)] and g_m == 0                   # the greedy chain stops at the root
+    # in-order drafts: identical to the chain walk
+    c[0] = [.1, .2, .9, .3, 0]
+    cc, tt = _mk(c, t)
+    assert decode.accept_mix_order(tt, cc, masked, drafts, 3)[0] == decode.accept_chain(tt[:4], cc[:4], masked[:4], drafts, 3)[0]
+    # the skipped draft matches after one verified draft: node 1 prefers draft 3
+    c[1] = [.3, .2, 0, .9, 0]
+    cc, tt = _mk(c, t)
+    acc, nxt, last = decode.accept_mix_order(tt, cc, masked, drafts, 3)
+    assert acc == [(2, 7), (3, 9), (1, 2)] and last == 5
+    # right token at a position that is no draft: no rescue
+    c[0] = [.1, .95, .9, .3, 0]
+    cc, tt = _mk(c, t)
+    assert decode.accept_mix_order(tt, cc, masked, drafts, 3)[0] == [(1, 5)]
+
+
+@pytest.mark.parametrize("seed,gen_len,block", [(1001, 64, 32), (8, 40, 8)])
+def test_mix_order_is_lossless_and_never_accepts_less_per_round(tiny, seed, gen_len, block):
+    """The mix-order tree keeps the output identical to stepwise decoding, accepts at most N+1
+    tokens per forward, and from any state accepts at least what the chain accepts."""
+    cfg, w = tiny
+    prompt = synth.gen_prompt(cfg, seed, 48)
+    ref, _ = decode.stepwise(w, cfg, prompt, gen_len, block)
+    for N in (1, 2, 3, 5):
+        trace = []
+        out, st = decode.ssd(w, cfg, prompt, gen_len, block, N, mix_order=True, trace=trace)
+        assert out == ref, f"N={N}"
+        hist = st["accept_hist"]
+        assert hist[0] == 0 and sum(a * h for a, h in enumerate(hist)) == gen_len
+        assert all(h == 0 for a, h in enumerate(hist) if a > N + 1)
+        for rec in trace:
+            n = len(rec["drafts"])
+            assert len(rec["t"]) == max(2 * n, n + 1)
+            chain_acc, _, _ = decode.accept_chain(rec["t"][:n + 1], rec["c"][:n + 1],
+                                                  [mk for _, mk in decode.build_chain(rec["tok"], rec["masked"], rec["drafts"])],
+                                                  rec["drafts"], N)
+            assert rec["accepted"][:len(chain_acc) - 1] == chain_acc[:-1] and len(rec["accepted"]) >= len(chain_acc)
+
+
+def test_mix_order_equals_chain_when_every_draft_verifies(tiny):
+    """Zero attention output projections: decoding runs left to right and every draft is verified,
+    so the extra nodes never fire and the forward count is the chain's closed form."""
+    cfg, w0 = tiny
+    w = dict(w0)
+    w["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w0["layers"]]
+    prompt = synth.gen_prompt(cfg, 3, 20)
+    for N in (3, 4):
+        out, st = decode.ssd(w, cfg, prompt, 64, 32, N, mix_order=True)
+        assert st["forwards"] == 2 * (1 + math.ceil(31 / (N + 1)))
+
+
 def test_build_chain_nodes():
     """Section 3.2.3: exactly N+1 nodes; node i holds the first i drafts."""
     nodes = decode.build_chain([9, 9, 9, 1], [True, True, True, False], [(2, 5), (0, 6)])

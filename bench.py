@@ -83,7 +83,7 @@ def main():
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         eng = binding.SSD(cfg, wg, max_seqs=nseq, max_seq_len=P + G, block=B, max_draft=N,
-                          max_rows=max(P, S, nseq * (N + 1) * B))
+                          max_rows=max(P, S, nseq * max(N + 1, 2 * N) * B))
         # ---- verification forward at prefix S, fixed block state with N drafts, every sequence of the batch
         note(f"context created; prefill of {nseq} x {S} positions")
         for i in range(nseq):
@@ -167,7 +167,10 @@ def main():
             eng.generate(prompts, B, B, N)                       # warm
             toks_ssd, st_ssd = eng.generate(prompts, G, B, N)
             toks_step, st_step = eng.generate(prompts, G, B, 0)
-            same = bool(np.array_equal(toks_ssd, toks_step))
+            eng.set_tree_mode(1)                                 # the mix-order tree (Section 5.2), for context
+            toks_mix, st_mix = eng.generate(prompts, G, B, N)
+            eng.set_tree_mode(0)
+            same = bool(np.array_equal(toks_ssd, toks_step) and np.array_equal(toks_mix, toks_step))
             GT = G * nseq                                        # tokens generated over the whole batch
             gen = dict(
                 ssd_tokens_per_s=GT / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_step["total_ms"] / 1e3),
@@ -175,7 +178,9 @@ def main():
                 accepted_per_forward=GT / max(sum(st_ssd["accept_hist"]), 1), accept_hist=st_ssd["accept_hist"][:N + 2],
                 ssd_decode_ms_per_forward=st_ssd["decode_ms"] / st_ssd["forwards"],
                 stepwise_ms_per_forward=st_step["decode_ms"] / st_step["forwards"],
-                ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"])
+                ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"],
+                mix_order_tokens_per_s=GT / (st_mix["total_ms"] / 1e3), mix_order_forwards=st_mix["forwards"],
+                mix_order_accept_hist=st_mix["accept_hist"][:N + 2])
 
     # ---- roofline arithmetic
     M = nseq * (N + 1) * B

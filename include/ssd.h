@@ -203,6 +203,19 @@ int ssd_set_kernel_path(ssd_ctx* ctx, int path);
  * previous value or an error. */
 int ssd_set_boundary_fusion(ssd_ctx* ctx, int on);
 
+/* Shape of the verification tree of ssd_verify_tree / ssd_generate:
+ * 0 = the greedy chain of n_draft + 1 nodes (Section 3.2.3), 1 = the mix-order
+ * tree (Section 5.2, Table 3): the chain plus, for every chain node but the last
+ * two, a node that skips the next draft and holds the one after it, 2 * n_draft
+ * nodes in all.  When a chain node's stepwise choice is the draft after the
+ * expected one (same candidates, different order) that draft is accepted and
+ * the extra node supplies one more token.  A forward then has up to
+ * 2 * n_draft * block rows per sequence: max_rows must allow for it.  The
+ * per-row debug outputs of ssd_step_out cover the chain nodes only.  The
+ * generated tokens are the same in both modes.  Default 0.  Returns the
+ * previous value or an error. */
+int ssd_set_tree_mode(ssd_ctx* ctx, int mode);
+
 /* HIP graphs: 1 = the kernel sequence of a forward is captured the second time
  * a launch shape (row count, node count, block length) occurs and replayed from
  * then on; 0 = every forward launches its kernels one by one.  Results are the

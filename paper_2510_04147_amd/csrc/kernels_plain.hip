@@ -57,6 +57,8 @@ __global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restr
             tok = s->tok[p];
             for (int j = 0; j < nd.j; ++j)
                 if (s->draft_pos[j] == p) tok = s->draft_tok[j];
+            // a mix-order node skips draft j and holds draft j + 1 instead (Section 5.2)
+            if (nd.extra >= 0 && s->draft_pos[nd.extra] == p) tok = s->draft_tok[nd.extra];
         }
         const int row = nd.row0 + p;
         row_tok[row] = tok;
@@ -485,6 +487,8 @@ __global__ __launch_bounds__(256) void k_lm_merge(const float* __restrict__ part
 // position and token; stops at the first mismatch; accepts the matched drafts
 // plus the choice of the node it stopped at; ranks that node's remaining
 // masked positions by confidence for the next drafts; commits to the state.
+// With mix-order nodes in the group (Section 5.2) a mismatch whose choice is
+// draft m+2 accepts that draft and ends at the node holding drafts 1..m, m+2.
 // ------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
                                                const float* __restrict__ row_conf, const int* __restrict__ row_arg,
@@ -495,7 +499,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     const ssd_step_out out = fw->out;
     if (g.mode != GM_DECODE) return;
     SeqState* s = &state[g.seq];
-    const int nd = g.n_nodes - 1;
+    const int nd = g.n_chain - 1;                         // drafts = chain nodes - 1
     const int blen = g.blen;
     const int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
     const int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
@@ -515,10 +519,12 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         }
     }
 
-    int m = 0, pstar = 0, tstar = 0;
+    // stepwise choice of a node over the positions still masked in `cur`: highest confidence, ties to
+    // the lowest position; leaves this lane's confidence in c
+    int pstar = 0, tstar = 0;
     float c = -1.f;
-    while (true) {
-        const int row = g.row0 + m * blen + lane;
+    auto choose = [&](int node) {
+        const int row = g.row0 + node * blen + lane;
         const bool valid = lane < blen && ((cur >> lane) & 1ull);
         c = valid ? row_conf[row] : -1.f;
         float bc = c;
@@ -530,7 +536,11 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
             if (oc > bc || (oc == bc && op < bp)) { bc = oc; bp = op; }
         }
         pstar = bp;
-        tstar = row_arg[g.row0 + m * blen + pstar];
+        tstar = row_arg[g.row0 + node * blen + pstar];
+    };
+    int m = 0;
+    while (true) {
+        choose(m);
         const int dp = __shfl(my_dpos, m, 64), dt = __shfl(my_dtok, m, 64);
         if (m < nd && pstar == dp && tstar == dt) {
             cur &= ~(1ull << pstar);
@@ -539,6 +549,20 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         }
         break;
     }
+    // mix order (Section 5.2): the choice is the draft after the expected one -> accept it and take
+    // one more token from the node that holds drafts 1..m and m+2; that node has no children
+    int last = m, res_pos = -1, res_tok = -1;
+    if (g.n_nodes > g.n_chain && m + 1 < nd) {
+        const int dp2 = __shfl(my_dpos, m + 1, 64), dt2 = __shfl(my_dtok, m + 1, 64);
+        if (pstar == dp2 && tstar == dt2) {
+            res_pos = pstar;
+            res_tok = tstar;
+            cur &= ~(1ull << pstar);
+            last = g.n_chain + m;
+            choose(last);
+        }
+    }
+    const int n_acc = m + 1 + (res_pos >= 0 ? 1 : 0);
     const unsigned long long rem = cur & ~(1ull << pstar);
     const int n_rem = __popcll(rem);
     const int n_next = min(g.n_draft_next, max(n_rem - 1, 0));
@@ -548,7 +572,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         const float cq = __shfl(c, qd, 64);
         if (((rem >> qd) & 1ull) && (cq > c || (cq == c && qd < lane))) ++rank;
     }
-    const int my_tok = row_arg[g.row0 + m * blen + (lane < blen ? lane : 0)];
+    const int my_tok = row_arg[g.row0 + last * blen + (lane < blen ? lane : 0)];
     StepResult* r = &result[g.seq];
     if (mine && rank < n_next) {
         r->next_pos[rank] = lane;
@@ -560,9 +584,10 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     }
     if (g.fresh) s->tok[lane] = mask_id;                  // SSD_MAX_BLOCK = 64 = one lane per position
     __syncthreads();
-    if (lane <= m) {
-        const int ap = lane < m ? my_dpos : pstar;
-        const int at = lane < m ? my_dtok : tstar;
+    if (lane < n_acc) {
+        // the matched drafts, then (mix order) the out-of-order draft, then the last node's own choice
+        const int ap = lane < m ? my_dpos : (lane == n_acc - 1 ? pstar : res_pos);
+        const int at = lane < m ? my_dtok : (lane == n_acc - 1 ? tstar : res_tok);
         r->acc_pos[lane] = ap;
         r->acc_tok[lane] = at;
         s->tok[ap] = at;
@@ -570,11 +595,11 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + lane] = at;
     }
     if (lane == 0) {
-        r->n_accept = m + 1;
+        r->n_accept = n_acc;
         r->n_next = n_next;
         s->masked = rem;
         s->n_draft = n_next;
-        if (out.n_accept) out.n_accept[gi] = m + 1;
+        if (out.n_accept) out.n_accept[gi] = n_acc;
         if (out.n_next) out.n_next[gi] = n_next;
     }
 }

@@ -186,6 +186,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->embed = w->embed; c->final_norm = w->final_norm;
     c->kernel_path = 1;
     c->fuse_boundary = 1;
+    c->tree_mode = 0;
     c->use_graphs = 0;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
@@ -270,6 +271,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_boundary_fusion(ss
     if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
     const int old = c->fuse_boundary;
     c->fuse_boundary = on;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_tree_mode(ssd_ctx* c, int mode) {
+    if (!c || (mode != 0 && mode != 1)) return SSD_EINVAL;
+    const int old = c->tree_mode;
+    c->tree_mode = mode;
     return old;
 }
 
@@ -486,16 +494,23 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     return SSD_OK;
 }
 
-// Appends a group (and its nodes) to a header; returns the rows it takes.
-static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_nodes, int n_draft_next, int fresh,
-                     int raw_off, int out_off) {
+// Mix-order nodes of a chain with n_draft drafts (Section 5.2): one per non-leaf chain node but the last.
+static int mix_nodes(const ssd_ctx* c, int n_draft) { return c->tree_mode == 1 && n_draft >= 2 ? n_draft - 1 : 0; }
+
+// Appends a group to a header: n_chain chain nodes (node j holds drafts 1..j), then n_extra mix-order
+// nodes (node m holds drafts 1..m and m+2); returns the rows it takes.
+static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_chain, int n_extra, int n_draft_next,
+                     int fresh, int raw_off, int out_off) {
     GroupDesc& g = hd.groups[hd.n_groups];
+    const int n_nodes = n_chain + n_extra;
     g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
-    g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.pad = 0;
+    g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.n_chain = n_chain;
     int vrows = hd.n_nodes ? hd.nodes[hd.n_nodes - 1].vrow0 + ((hd.nodes[hd.n_nodes - 1].blen + 63) & ~63) : 0;
     for (int j = 0; j < n_nodes; ++j) {
         NodeDesc& nd = hd.nodes[hd.n_nodes++];
-        nd.seq = seq; nd.row0 = hd.M + j * blen; nd.blen = blen; nd.S = S; nd.group = hd.n_groups; nd.j = j;
+        nd.seq = seq; nd.row0 = hd.M + j * blen; nd.blen = blen; nd.S = S; nd.group = hd.n_groups;
+        nd.j = j < n_chain ? j : j - n_chain;
+        nd.extra = j < n_chain ? -1 : j - n_chain + 1;
         nd.write_kv = mode != GM_DECODE;
         nd.vrow0 = vrows;
         vrows += (blen + 63) & ~63;
@@ -521,7 +536,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_prefill_kv(ssd_ctx* c,
         if (tokens[i] < 0 || tokens[i] >= d.V) { set_err(c, "prefill: token id %d out of range", tokens[i]); return SSD_ERANGE; }
     FwdHeader hd;
     memset(&hd, 0, sizeof hd);
-    add_group(hd, seq, GM_RAW, n, pos0, 1, 0, 0, 0, -1);
+    add_group(hd, seq, GM_RAW, n, pos0, 1, 0, 0, 0, 0, -1);
     int rc = run_forward(c, hd, tokens, n, nullptr, 0, nullptr);
     if (rc == SSD_OK) c->cached_len[seq] = pos0 + n;
     return rc;
@@ -581,8 +596,8 @@ static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, cons
             s.draft_pos[j] = q;
             s.draft_tok[j] = t;
         }
-        if (hd.M + (nd + 1) * bl > d.max_rows) { set_err(c, "%s: forward exceeds max_rows", who); return SSD_ERANGE; }
-        add_group(hd, seq, GM_DECODE, bl, pos0[i], nd + 1, n_draft_next, 0, 0, -1);
+        if (hd.M + (nd + 1 + mix_nodes(c, nd)) * bl > d.max_rows) { set_err(c, "%s: forward exceeds max_rows", who); return SSD_ERANGE; }
+        add_group(hd, seq, GM_DECODE, bl, pos0[i], nd + 1, mix_nodes(c, nd), n_draft_next, 0, 0, -1);
     }
     return run_forward(c, hd, nullptr, 0, ups, n, out);
 }
@@ -656,7 +671,8 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
             for (int i = 0; i < n; ++i) {
                 if (phase[i] == DONE) continue;
                 const int bl = std::min(block, gen_len - blk[i] * block);
-                rows += phase[i] == APPEND ? bl : ((phase[i] == FRESH ? 0 : n_dr[i]) + 1) * bl;
+                const int ndr = phase[i] == FRESH ? 0 : n_dr[i];
+                rows += phase[i] == APPEND ? bl : (ndr + 1 + mix_nodes(c, ndr)) * bl;
             }
             for (int i = 0; i < n; ++i) {
                 if (phase[i] != APPEND || blk[i] + 1 >= n_blocks) continue;
@@ -670,16 +686,17 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
                 const int bl = std::min(block, gen_len - blk[i] * block);
                 if (pass == 0 && phase[i] != APPEND) {
                     if (phase[i] == FRESH) { n_masked[i] = bl; n_dr[i] = 0; }
-                    add_group(hd, i, GM_DECODE, bl, c->cached_len[i], n_dr[i] + 1, draft_depth, phase[i] == FRESH, 0, -1);
+                    add_group(hd, i, GM_DECODE, bl, c->cached_len[i], n_dr[i] + 1, mix_nodes(c, n_dr[i]), draft_depth,
+                              phase[i] == FRESH, 0, -1);
                     any_decode = true;
                 } else if (pass == 0 && fuse[i]) {
                     const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
                     n_masked[i] = bln;
                     n_dr[i] = 0;
-                    add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, draft_depth, 1, 0, -1);
+                    add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, 0, draft_depth, 1, 0, -1);
                     any_decode = true;
                 } else if (pass == 1 && phase[i] == APPEND) {
-                    add_group(hd, i, GM_APPEND, bl, c->cached_len[i], 1, 0, 0, 0, blk[i] * block);
+                    add_group(hd, i, GM_APPEND, bl, c->cached_len[i], 1, 0, 0, 0, 0, blk[i] * block);
                 }
             }
         if (hd.M > d.max_rows) { set_err(c, "generate: forward exceeds max_rows"); return done(SSD_ERANGE); }
@@ -696,8 +713,8 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
             const int i = g.seq;
             if (g.mode == GM_DECODE) {
                 const StepResult& r = c->host_result[i];
-                if (r.n_accept < 1 || r.n_accept > g.n_nodes || r.n_accept > n_masked[i]) {
-                    set_err(c, "generate: acceptance kernel returned %d for %d nodes", r.n_accept, g.n_nodes);
+                if (r.n_accept < 1 || r.n_accept > g.n_chain || r.n_accept > n_masked[i]) {
+                    set_err(c, "generate: acceptance kernel returned %d for a chain of %d nodes", r.n_accept, g.n_chain);
                     return done(SSD_EHIP);
                 }
                 sta.accept_hist[r.n_accept]++;

@@ -9,7 +9,8 @@
 #include "../../include/ssd.h"
 
 #define SSD_MAX_SEQS 16
-#define SSD_MAX_NODES (SSD_MAX_SEQS * (SSD_MAX_DRAFT + 1))
+// per sequence: the largest tree (2 * draft length nodes with mix order) plus a KV-append node
+#define SSD_MAX_NODES (SSD_MAX_SEQS * (2 * SSD_MAX_DRAFT + 1))
 #define SSD_MAX_SPLIT 8
 
 // ---- forward descriptor (host-built, copied to the device before each forward)
@@ -25,12 +26,13 @@ struct GroupDesc {
     int fresh;      // GM_DECODE: block starts now, state = all masked, no drafts
     int out_off;    // GM_APPEND: offset into the device token output, or -1
     int node0;      // index of the group's first node
-    int pad;
+    int n_chain;    // GM_DECODE: nodes 0 .. n_chain-1 are the chain, the rest mix-order nodes
 };
 
 struct NodeDesc {
     int seq, row0, blen, S;
-    int group, j;   // j = index of the node inside its group = number of drafts written in
+    int group, j;   // j = number of leading drafts written in (= the node's index along the chain)
+    int extra;      // mix-order node: index of the one further draft written in (j + 1), else -1
     int write_kv;
     int vrow0;      // 64-aligned start of the node's rows in the own-key / own-value buffers
 };
@@ -77,8 +79,10 @@ struct Dims {
     size_t esz() const { return dtype == SSD_F32 ? 4 : 2; }
     // positions allocated per cache slot: whole 64-position tiles, so tile loads stay in bounds
     int seq_stride() const { return (max_seq_len + 63) & ~63; }
+    // most nodes one forward of this context can hold
+    int max_nodes() const { return max_seqs * ((2 * max_draft > max_draft + 1 ? 2 * max_draft : max_draft + 1) + 1); }
     // rows of the own-key / own-value buffers: every node starts on a 64-row boundary
-    int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * SSD_MAX_NODES; }
+    int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * max_nodes(); }
 };
 
 // Keys and values, cached or of the forward's own rows, are stored per KV head in the order the
@@ -160,6 +164,7 @@ struct ssd_ctx {
     hipStream_t stream;
     int kernel_path;
     int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
+    int tree_mode;       // 0 = greedy chain (Section 3.2.3), 1 = mix-order tree (Section 5.2)
     // HIP graphs of the forward's kernel sequence, one per launch shape.  Everything that changes
     // between forwards of one shape (tokens, prefix lengths, drafts, output pointers) lives in
     // device memory, so a shape's second forward is captured and later ones replay the graph.

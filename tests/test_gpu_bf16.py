@@ -104,6 +104,14 @@ def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
         out, st = eng.generate([prompt], 64, 32, N)
         assert np.array_equal(out, base), f"N={N}"
         print(f"N={N}: forwards {st['forwards']} accept_hist {st['accept_hist'][:N + 2]}")
+    # the mix-order tree (8 nodes for N = 4, MFMA path) changes the rounds, not the tokens
+    eng.set_tree_mode(1)
+    try:
+        out, st = eng.generate([prompt], 64, 32, 4)
+    finally:
+        eng.set_tree_mode(0)
+    assert np.array_equal(out, base), "mix order"
+    print(f"mix order N=4: forwards {st['forwards']} accept_hist {st['accept_hist'][:6]}")
     # two sequences at once, different prompt lengths
     p2 = synth.gen_prompt(cfg, 77, 61)
     solo, _ = eng.generate([p2], 64, 32, 0)

@@ -109,6 +109,62 @@ def test_block_boundary_fusion_changes_passes_not_tokens(setup):
         eng.set_boundary_fusion(1)
 
 
+def test_mix_order_tree_on_gpu(setup):
+    """Section 5.2: with the mix-order tree the tokens stay those of stepwise decoding; per round
+    the walk accepts what the oracle's walk accepts on the same model; a single verification with
+    out-of-order drafts accepts the later draft and one more token."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=256, block=32, max_draft=8, max_rows=16 * 32)
+    try:
+        prompt = synth.gen_prompt(cfg, 1001, 64)
+        base, _ = eng.generate([prompt], 64, 32, 0)
+        assert eng.set_tree_mode(1) == 0
+        for N in (1, 2, 3, 5, 8):
+            out, st = eng.generate([prompt], 64, 32, N)
+            assert np.array_equal(out, base), f"mix order, N={N}"
+            ref, so = decode.ssd(w, cfg, prompt, 64, 32, N, mix_order=True)
+            if list(base[0]) == ref:                      # no near-tie anywhere: the rounds must agree too
+                assert st["forwards"] == so["forwards"] and st["accept_hist"][:N + 2] == so["accept_hist"][:N + 2], N
+            assert eng.set_tree_mode(0) == 1
+            _, sg = eng.generate([prompt], 64, 32, N)
+            assert st["forwards"] <= sg["forwards"] + 2   # the extra nodes only ever add accepted tokens per round
+            assert eng.set_tree_mode(1) == 0
+        # one forward, teacher forced from the oracle's first verification round of a fresh block,
+        # with the first two drafts swapped: the chain accepts 1 token, the mix-order tree 2 or more
+        trace = []
+        decode.ssd(w, cfg, prompt, 32, 32, 3, trace=trace, max_forwards=2)
+        rec = trace[1]
+        assert len(rec["drafts"]) == 3
+        swapped = [rec["drafts"][1], rec["drafts"][0], rec["drafts"][2]]
+        eng.reset(0)
+        eng.prefill_kv(0, prompt, 0)
+        masked = sum(1 << p for p, mk in enumerate(rec["masked"]) if mk)
+        got = {}
+        for mode in (0, 1):
+            eng.set_tree_mode(mode)
+            o = eng.new_out(1)
+            eng.verify_tree([0], [rec["tok"]], [masked], [rec["S"]], [swapped], 3, o)
+            got[mode] = o.host()
+        nodes = decode.build_mix_order(rec["tok"], rec["masked"], swapped)
+        preds = [decode._node_forward(w, cfg, nt, rec["S"], _oracle_cache(w, cfg, prompt), torch.float64) for nt, _ in nodes]
+        exp_mix, nxt_mix, _ = decode.accept_mix_order([p[0] for p in preds], [p[2] for p in preds], [mk for _, mk in nodes], swapped, 3)
+        exp_chain, _, _ = decode.accept_chain([p[0] for p in preds[:4]], [p[2] for p in preds[:4]], [mk for _, mk in nodes[:4]], swapped, 3)
+        for mode, exp in ((0, exp_chain), (1, exp_mix)):
+            n = int(got[mode]["n_accept"][0])
+            acc = list(zip(got[mode]["acc_pos"][0][:n].tolist(), got[mode]["acc_tok"][0][:n].tolist()))
+            assert acc == exp, (mode, acc, exp)
+        assert len(exp_mix) >= len(exp_chain)
+        nn = int(got[1]["n_next"][0])
+        assert list(zip(got[1]["next_pos"][0][:nn].tolist(), got[1]["next_tok"][0][:nn].tolist())) == nxt_mix
+    finally:
+        eng.close()
+
+
+def _oracle_cache(w, cfg, prompt):
+    return decode._prefill(w, cfg, prompt, torch.float64)
+
+
 def test_graph_replays_match_eager_launches(setup):
     """A launch shape's forward is captured into a HIP graph the second time it occurs and replayed
     afterwards.  Every replay, with the program's own eager work and synchronisations in between and

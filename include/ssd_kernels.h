@@ -26,6 +26,17 @@ extern "C" {
  * Asynchronous on the context's stream.  Errors: SSD_EINVAL, SSD_ERANGE. */
 int ssd_k_linear(ssd_ctx* ctx, int which, int layer, const void* x, int M, void* out);
 
+/* The acceptance step alone (Section 3.2.4; with ssd_set_tree_mode(ctx, 1) the mix-order walk of
+ * Section 5.2) on caller-supplied model outputs.  Arguments as ssd_verify_tree, without prefix
+ * lengths; row_conf / row_argmax are device arrays with one entry per row of the forward the call
+ * describes: sequences in call order, per sequence the chain nodes 0 .. n_draft[i] and then the
+ * mix-order nodes, block_len (default: the context's block) rows per node.  Writes `out` and the
+ * context's block state exactly as the forward's last kernel does.  Asynchronous on the
+ * context's stream.  Errors as ssd_verify_tree. */
+int ssd_k_accept(ssd_ctx* ctx, int n, const int* seqs, const int32_t* block_tok, const uint64_t* masked,
+                 const int* block_len, const int32_t* draft_pos, const int32_t* draft_tok, const int* n_draft,
+                 int n_draft_next, const float* row_conf, const int32_t* row_argmax, const ssd_step_out* out);
+
 /* Streams `bytes` of device memory with the access pattern of the GEMM's weight stream
  * (work_groups x waves_per_wg waves, `depth` 16-byte loads in flight per lane: 4, 8 or 16):
  * the HBM read rate the chip sustains, i.e. the practical ceiling of the roofline.

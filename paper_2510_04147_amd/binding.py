@@ -21,7 +21,7 @@ SSD_F32, SSD_BF16 = 0, 1
 EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd_cached_len", "ssd_prefill_kv",
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_graphs", "ssd_set_tree_mode",
            "ssd_profile_begin",
-           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear",
+           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
            "ssd_debug_stream_read"]
 LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
@@ -73,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.ssd_generate.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.c_void_p, C.c_int, C.c_int, C.c_int,
                                  C.c_void_p, C.POINTER(SsdStats)]
     lib.ssd_set_kernel_path.argtypes = [C.c_void_p, C.c_int]
+    lib.ssd_k_accept.argtypes = [C.c_void_p, C.c_int] + [C.c_void_p] * 7 + [C.c_int, C.c_void_p, C.c_void_p,
+                                                                              C.POINTER(SsdStepOut)]
     lib.ssd_set_boundary_fusion.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_graphs.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
@@ -267,6 +269,23 @@ class SSD:
                      accept_hist=list(st.accept_hist), decode_ms=st.decode_ms, kv_ms=st.kv_ms,
                      total_ms=st.total_ms)
         return out, stats
+
+    def k_accept(self, seqs, block_tok, masked, drafts, n_draft_next, row_conf, row_argmax, out, block_len=None):
+        """The acceptance step alone on device arrays row_conf (float32) / row_argmax (int32), one entry per row."""
+        n, sq, bt, mk, _, bl = self._block_args(seqs, block_tok, masked, [0] * len(seqs), block_len)
+        md = max(self.max_draft, 1)
+        dp, dtk = np.zeros((n, md), dtype=np.int32), np.zeros((n, md), dtype=np.int32)
+        nd = np.zeros(n, dtype=np.int32)
+        for i, dr in enumerate(drafts):
+            nd[i] = len(dr)
+            for j, (q, t) in enumerate(dr[:md]):
+                dp[i, j], dtk[i, j] = q, t
+        assert row_conf.dtype == torch.float32 and row_argmax.dtype == torch.int32
+        assert row_conf.is_contiguous() and row_argmax.is_contiguous() and row_conf.device == self.device
+        self._chk(self.lib.ssd_k_accept(self.h, n, sq.ctypes.data, bt.ctypes.data, mk.ctypes.data,
+                                        bl.ctypes.data if bl is not None else None, dp.ctypes.data, dtk.ctypes.data,
+                                        nd.ctypes.data, n_draft_next, row_conf.data_ptr(), row_argmax.data_ptr(),
+                                        C.byref(out.c)))
 
     def k_linear(self, which, layer, x, out):
         """One linear step on caller-supplied rows x [M, K] (device tensor of the model dtype)."""

@@ -379,7 +379,7 @@ static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void*
 // Runs one forward over the groups in `hd` (decode groups first).  raw / n_raw:
 // tokens of GM_RAW groups; ups: block states to upload first.
 static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int n_raw, const Upload* ups, int n_ups,
-                       const ssd_step_out* out) {
+                       const ssd_step_out* out, const float* k_conf = nullptr, const int32_t* k_arg = nullptr) {
     const Dims& d = c->dm;
     hipStream_t st = c->stream;
     // ---- stage and upload the descriptor
@@ -406,6 +406,16 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     c->stage_used[slot] = true;
 
     const int M = hd.M, ML = hd.M_logits;
+    if (k_conf) {
+        // kernel-level entry: the caller supplies every row's confidence and arg-max; only the
+        // acceptance kernel runs
+        HIPCHK(c, hipMemcpyAsync(c->b.row_conf, k_conf, (size_t)ML * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(c, hipMemcpyAsync(c->b.row_arg, k_arg, (size_t)ML * 4, hipMemcpyDeviceToDevice, st));
+        HIPCHK(c, hipMemsetAsync(c->b.row_max, 0, (size_t)ML * 4, st));
+        launch_accept(c, hd.n_groups, st);
+        HIPCHK(c, hipGetLastError());
+        return SSD_OK;
+    }
     int max_blen = 0;
     bool any_write_kv = false;
     for (int i = 0; i < hd.n_nodes; ++i) {
@@ -546,10 +556,12 @@ static int popcount64(uint64_t x) { return __builtin_popcountll(x); }
 
 static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, const int32_t* block_tok,
                        const uint64_t* masked, const int* pos0, const int* block_len, const int32_t* draft_pos,
-                       const int32_t* draft_tok, const int* n_draft, int n_draft_next, const ssd_step_out* out) {
+                       const int32_t* draft_tok, const int* n_draft, int n_draft_next, const ssd_step_out* out,
+                       const float* k_conf = nullptr, const int32_t* k_arg = nullptr) {
     if (!c) return SSD_EINVAL;
     const Dims& d = c->dm;
-    if (n < 1 || !seqs || !block_tok || !masked || !pos0) { set_err(c, "%s: null argument or n < 1", who); return SSD_EINVAL; }
+    const bool accept_only = k_conf != nullptr;          // no forward: prefix lengths play no part
+    if (n < 1 || !seqs || !block_tok || !masked || (!pos0 && !accept_only)) { set_err(c, "%s: null argument or n < 1", who); return SSD_EINVAL; }
     if (n > d.max_seqs) { set_err(c, "%s: n %d exceeds max_seqs", who, n); return SSD_ERANGE; }
     if (n_draft_next < 0 || n_draft_next > d.max_draft) { set_err(c, "%s: n_draft_next out of range", who); return SSD_ERANGE; }
     FwdHeader hd;
@@ -563,11 +575,12 @@ static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, cons
         seen[seq] = true;
         const int bl = block_len ? block_len[i] : d.block;
         if (bl < 1 || bl > d.block) { set_err(c, "%s: block_len %d out of range", who, bl); return SSD_ERANGE; }
-        if (pos0[i] != c->cached_len[seq]) {
-            set_err(c, "%s: pos0 %d is not the cached prefix length %d of seq %d", who, pos0[i], c->cached_len[seq], seq);
+        const int p0 = accept_only ? 0 : pos0[i];
+        if (!accept_only && p0 != c->cached_len[seq]) {
+            set_err(c, "%s: pos0 %d is not the cached prefix length %d of seq %d", who, p0, c->cached_len[seq], seq);
             return SSD_ESTATE;
         }
-        if ((long long)pos0[i] + bl > d.max_seq_len) { set_err(c, "%s: block exceeds max_seq_len", who); return SSD_ERANGE; }
+        if ((long long)p0 + bl > d.max_seq_len) { set_err(c, "%s: block exceeds max_seq_len", who); return SSD_ERANGE; }
         const uint64_t mk = masked[i];
         if (bl < 64 && (mk >> bl)) { set_err(c, "%s: masked bits beyond block_len", who); return SSD_EINVAL; }
         const int nm = popcount64(mk);
@@ -597,9 +610,9 @@ static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, cons
             s.draft_tok[j] = t;
         }
         if (hd.M + (nd + 1 + mix_nodes(c, nd)) * bl > d.max_rows) { set_err(c, "%s: forward exceeds max_rows", who); return SSD_ERANGE; }
-        add_group(hd, seq, GM_DECODE, bl, pos0[i], nd + 1, mix_nodes(c, nd), n_draft_next, 0, 0, -1);
+        add_group(hd, seq, GM_DECODE, bl, p0, nd + 1, mix_nodes(c, nd), n_draft_next, 0, 0, -1);
     }
-    return run_forward(c, hd, nullptr, 0, ups, n, out);
+    return run_forward(c, hd, nullptr, 0, ups, n, out, k_conf, k_arg);
 }
 
 extern "C" __attribute__((visibility("default"))) int ssd_draft(ssd_ctx* c, int n, const int* seqs, const int32_t* block_tok, const uint64_t* masked,
@@ -739,6 +752,18 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
 }
 
 // ---------------------------------------------------------- kernel-level entry
+extern "C" __attribute__((visibility("default"))) int ssd_k_accept(ssd_ctx* c, int n, const int* seqs, const int32_t* block_tok,
+                                                                   const uint64_t* masked, const int* block_len,
+                                                                   const int32_t* draft_pos, const int32_t* draft_tok,
+                                                                   const int* n_draft, int n_draft_next,
+                                                                   const float* row_conf, const int32_t* row_argmax,
+                                                                   const ssd_step_out* out) {
+    if (!c) return SSD_EINVAL;
+    if (!n_draft || !row_conf || !row_argmax) { set_err(c, "ssd_k_accept: null argument"); return SSD_EINVAL; }
+    return step_common(c, "ssd_k_accept", n, seqs, block_tok, masked, nullptr, block_len, draft_pos, draft_tok, n_draft,
+                       n_draft_next, out, row_conf, row_argmax);
+}
+
 extern "C" __attribute__((visibility("default"))) int ssd_k_linear(ssd_ctx* c, int which, int layer, const void* x,
                                                                    int M, void* out) {
     if (!c) return SSD_EINVAL;

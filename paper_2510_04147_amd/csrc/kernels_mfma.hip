@@ -470,7 +470,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 // ------------------------------------------------------------------------
 // launcher
 // ------------------------------------------------------------------------
-template <int WN, int WK, int R, int MT, int EPI, int NCH>
+template <int WN, int WK, int R, int MT, int EPI, int NCH, int POLICY = 0>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
                        int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
     constexpr int KC = WK * 32, ROWS = MT * 32, LDW = KC + 8;
@@ -481,7 +481,7 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
                                        : (size_t)(WN / 2 + 1) * MT * 16 * 64 * 4;
     constexpr size_t smem = xbytes > rbytes ? xbytes : rbytes;
     static_assert(smem <= 160 * 1024, "LDS budget");
-    auto kern = k_gemm_mfma<WN, WK, R, MT, EPI, NCH>;
+    auto kern = k_gemm_mfma<WN, WK, R, MT, EPI, NCH, POLICY>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -505,6 +505,11 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
     case v:                                                                                                     \
         return launch_one<WN, WK, R, v, EPI, NCH>(X, Wp, out, M, N, K, split, split_stride, mask_id,  \
                                                n_tiles_out, m_chunks, st);
+    // more than one row chunk: every chunk re-reads the weights, so they are loaded with the default
+    // cache policy (kernel option bit 5) and the later chunks find them in L2 / the Infinity Cache
+    if (mt == 5 && m_chunks > 1)
+        return launch_one<WN, WK, R, 5, EPI, NCH, 32>(X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out,
+                                                      m_chunks, st);
     switch (mt) {
         SSD_MT_CASE(1)
         SSD_MT_CASE(2)

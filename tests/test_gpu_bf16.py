@@ -84,6 +84,27 @@ def test_mfma_path_teacher_forced_against_oracle(shallow8b):
     assert tot["tok_exempt"] <= 0.10 * tot["rows"]
 
 
+def test_mfma_path_ragged_block_and_separate_rotary_kernel(shallow8b):
+    """Blocks that fill a 32-row tile only partly (block 24, last block 8), once with the rotary stage
+    inside the attention kernel (path 1) and once as a kernel of its own (path 2): both against the
+    oracle, and bit-identical to each other."""
+    cfg, w, wg, eng, prompt, sigma = shallow8b
+    tol = parity_util.bf16_tolerances(sigma)
+    outs = {}
+    try:
+        for path in (1, 2):
+            eng.set_kernel_path(path)
+            ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 32, 24, 3, torch.float32, max_forwards=6, **tol)
+            print(f"path {path}, block 24:", tot)
+            assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
+            outs[path], _ = eng.generate([prompt], 56, 24, 3)
+    finally:
+        eng.set_kernel_path(1)
+    assert np.array_equal(outs[1], outs[2])
+    base, _ = eng.generate([prompt], 56, 24, 0)
+    assert np.array_equal(outs[1], base)
+
+
 def test_plain_path_teacher_forced_against_oracle(shallow8b):
     cfg, w, wg, eng, prompt, sigma = shallow8b
     eng.set_kernel_path(0)

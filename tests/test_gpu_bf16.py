@@ -140,6 +140,26 @@ def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
     assert np.array_equal(both[0], base[0]) and np.array_equal(both[1], solo[0])
 
 
+def test_graph_replay_of_the_mfma_forward(shallow8b):
+    """HIP-graph replay (off by default) of the bf16 forward with its MFMA kernels: a context on a side
+    stream, graphs on, must generate the same tokens and run the same number of forwards."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, eng, prompt, _ = shallow8b
+    base, st0 = eng.generate([prompt], 64, 32, 4)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=512, block=32, max_draft=4, max_rows=320)
+        try:
+            g.set_graphs(1)
+            for rep in range(3):                       # first run captures, later runs replay every shape
+                out, st = g.generate([prompt], 64, 32, 4)
+                assert np.array_equal(out, base), rep
+                assert st["forwards"] == st0["forwards"] and st["accept_hist"] == st0["accept_hist"]
+        finally:
+            g.close()
+
+
 def test_node_rows_independent_of_batch_shape(shallow8b):
     """A node's rows are bit-identical alone (M=32) and inside a 5-node forward (M=160)."""
     cfg, w, wg, eng, _, _ = shallow8b

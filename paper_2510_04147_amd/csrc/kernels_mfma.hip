@@ -7,13 +7,18 @@
 //     order: fragment (nt, ks) = rows [32nt, 32nt+32) x columns [16ks, 16ks+16)
 //     is one contiguous 1 KiB block laid out lane by lane, so a wave's load
 //     instruction reads 1 KiB of consecutive bytes and a wave streams a
-//     contiguous region straight into registers (no LDS round trip);
+//     contiguous region straight into registers (no LDS round trip), with
+//     non-temporal loads, so that the stream does not evict the activations
+//     from L2; the gate/up matrix interleaves gate and up rows per 16 channels,
+//     which makes SwiGLU lane-local;
 //   * the weight fragment is the A operand of v_mfma_f32_32x32x16_bf16, the
 //     activations are the B operand, so each lane ends up with 4 consecutive
 //     output columns of one row: vector stores, lane-local SwiGLU and LM-head
 //     reductions;
-//   * activations are staged through LDS in K chunks, double buffered, shared
-//     by all waves of the work-group;
+//   * activations are staged through LDS in K chunks (a three-stage ring),
+//     shared by all waves of the work-group;
+//   * grids aim at one work-group per CU (256) and are XCD-aware: with split-K
+//     the work-groups of one XCD read the same k-slice of the activations;
 //   * K can be split inside a work-group (waves reduce through LDS) and across
 //     work-groups (partial sums to a workspace, summed in a fixed order by the
 //     consumer).  Both splits depend on the weight shape only, never on M, and
@@ -83,8 +88,8 @@ void launch_pack_weights(const void* src, void* dst, int N, int K, int gate_rows
 // Software pipeline, all statically indexed:
 //   weights      a ring of DW chunks in registers per wave: the fragment loads
 //                of chunk c+DW-1 are issued while chunk c is multiplied;
-//   activations  loads of chunk c+PX are issued into a register ring, chunk c+1
-//                is written to the other half of a two-stage LDS buffer while
+//   activations  loads of chunk c+PX are issued into a register ring, chunk c+2
+//                is written to the free stage of a three-stage LDS ring while
 //                chunk c is multiplied, one barrier per chunk.
 // With the chunk count known at compile time (NCH > 0) the loop is straight-line
 // code, so the compiler's wait counts are exact; NCH = 0 is the same pipeline as
@@ -607,23 +612,22 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
 
 // ------------------------------------------------------------------------
 // a4: shared-prefix bidirectional attention on the matrix cores.
-// One wave per (node, query head, 32-row query tile).  Keys are walked in
-// tiles of 32, first the sequence's cached prefix [0,S), then the node's own
-// rows; online softmax in fp32.
+// One work-group of ATTN_WAVES waves per (node, query head, 32-row query tile).
+// Keys are walked in tiles of 32, first the sequence's cached prefix [0,S), then
+// the node's own rows; wave w takes tiles w, w + ATTN_WAVES, ...; online softmax
+// in fp32; the waves' partial results are merged through LDS in wave order.
 //   S^T[key][q] = K Q^T     : A = K fragment (rows = keys), B = Q fragment
 //   O^T[d][q]  += V^T P^T   : A = V^T fragment (rows = d),  B = P^T fragment
 // With q on the MFMA column axis every softmax statistic (running max, sum,
 // rescale factor) is per lane, and the P^T values a lane computed are exactly
 // its B-operand values for the second product, so nothing crosses lanes except
 // one xor-32 exchange per tile.  The k index of the second product is the key;
-// lane half lh supplies keys {8g + 4lh + 0..3 : g = 2st, 2st+1} of step st, which
-// are two runs of 4 consecutive positions in the position-contiguous value
-// layout (two 8-byte loads).
+// lane half lh supplies keys {8g + 4lh + 0..3 : g = 2st, 2st+1} of step st: the
+// value layout stores exactly those eight next to each other, so keys and values
+// both arrive as one 16-byte load per lane and fragment.
 // The tile order depends on S and the block length only, so a row's result does
 // not depend on how many nodes the forward holds.
 // ------------------------------------------------------------------------
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-
 #define ATTN_WAVES 8   // waves per (node, head, query tile): wave w takes key tiles w, w+8, ...
 
 // FUSED: the kernel starts from the QKV projection's fp32 partial sums instead of ready q / k / v: it

@@ -159,6 +159,31 @@ def main():
         eng.profile_end()
         n_prof = max(3, args.steps // 5)
 
+        # ---- the dominant kernel alone, for comparison: back to back through the kernel-level entry point,
+        # one event pair around all launches; every layer's gate/up weights in turn, so the weights stream
+        # from HBM, and a pool of activation matrices larger than the L2s.  (Inside the forward the kernel
+        # is a few us faster: there HBM rests while the small kernels around it run.)
+        gu_iso_us = None
+        if cfg["dtype"] == "bf16":
+            note("gate/up GEMM back to back")
+            Mrows = nseq * (N + 1) * B
+            pool = torch.randn(48, Mrows, cfg["d_model"], device="cuda").to(torch.bfloat16)
+            act = torch.empty(Mrows, cfg["d_ffn"], dtype=torch.bfloat16, device="cuda")
+            L = cfg["n_layers"]
+            for l in range(L):
+                eng.k_linear(binding.LIN_GU, l, pool[l % 48], act)
+            reps = 3
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            stream.synchronize()
+            g0.record(stream)
+            for r in range(reps):
+                for l in range(L):
+                    eng.k_linear(binding.LIN_GU, l, pool[(r * L + l) % 48], act)
+            g1.record(stream)
+            stream.synchronize()
+            gu_iso_us = 1e3 * g0.elapsed_time(g1) / (reps * L)
+            del pool, act
+
         # ---- whole generation of the workload: SSD and stepwise
         gen = {}
         if not args.no_generate:
@@ -194,7 +219,7 @@ def main():
     gu = prof.get("gemm_gate_up_swiglu", dict(launches=0, ms=0.0))
     gu_bytes = 2 * F * d * esz + M * d * esz + M * F * esz     # weights + activations in + SwiGLU out
     gu_flops = 2.0 * M * 2 * F * d
-    gu_us = 1e3 * gu["ms"] / max(gu["launches"], 1)
+    gu_us = 1e3 * gu["ms"] / max(gu["launches"], 1)          # inside the forward, one event pair per launch
     gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9 if gu_us > 0 else 0.0
     gu_tflops = gu_flops / (gu_us * 1e-6) / 1e12 if gu_us > 0 else 0.0
     traffic = read_measured_traffic(args.workload)
@@ -203,12 +228,13 @@ def main():
     if hbm_bound:
         roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"]}
+                "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "launches_timed": gu["launches"],
+                "us_per_launch_back_to_back_alone": gu_iso_us}
     else:
         roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": gu_tflops,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic, "flops_per_launch": gu_flops, "achieved_GBs": gu_gbs, "us_per_launch": gu_us,
-                "launches_timed": gu["launches"]}
+                "launches_timed": gu["launches"], "us_per_launch_back_to_back_alone": gu_iso_us}
     line = {
         "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
         "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

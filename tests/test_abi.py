@@ -67,3 +67,6 @@ def test_config_validation_needs_no_gpu(lib):
     rc = lib.ssd_create(ctypes.byref(good), ctypes.byref(w), ctypes.c_void_p(256), 1 << 30, None, ctypes.byref(h))
     assert rc == -1                            # null weight pointers
     assert lib.ssd_destroy(None) == -1
+    # the option setters reject a null context without touching the device
+    for name in ("ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_tree_mode", "ssd_set_graphs"):
+        assert getattr(lib, name)(None, 1) == -1, name

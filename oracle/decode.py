@@ -11,6 +11,11 @@
                predictions as the next drafts.
   bruteforce   stepwise decoding with no cache: the whole sequence is
                recomputed under the block-causal mask for every token.
+  cross block  ssd_cross_block: drafts may cover every remaining position of the
+               current block; the leaf then holds the finished block and the
+               same forward also predicts the next block from it (Section 3.2.2:
+               once fewer than N positions remain, candidates come from the next
+               block).  Restricted to that one step across the boundary.
   mix order    ssd(..., mix_order=True): the greedy chain plus one extra node per
                non-leaf chain node that skips the next draft (Section 5.2,
                Table 3): when node m's stepwise choice is draft m+2 instead of
@@ -166,6 +171,14 @@ def _prefill(w, cfg, prompt, dtype):
     return cache
 
 
+def _cache_with(cache, kv):
+    """A copy of the cache with one more segment appended (the original is left alone)."""
+    c = KVCache(len(cache.k))
+    c.k, c.v = list(cache.k), list(cache.v)
+    c.append(kv)
+    return c
+
+
 def _node_forward(w, cfg, tok, S, cache, dtype):
     logits, _ = forward_segment(w, cfg, tok, S, cache, dtype)
     return predict(logits, cfg["mask_id"])
@@ -238,6 +251,106 @@ def ssd(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None
         cache.append(kv)
         kv_passes += 1
         out += tok
+    return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
+
+
+def ssd_cross_block(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64, trace=None):
+    """SSD whose last round of a block reaches into the next block (Section 3.2.2).
+
+    As ssd(), except that while a next block exists the drafts may cover ALL remaining masked
+    positions of the current block (up to n_draft).  The chain's leaf then holds the finished
+    block.  The same forward evaluates the next block, all masked, behind that leaf (its keys and
+    values are those of the finished block: exactly the block-start forward stepwise decoding
+    would run next).  If every draft verifies, the block is finished, its KV is kept, and the
+    next block starts with the stepwise choice and the drafts read off that evaluation: the
+    boundary costs no forward of its own.  Otherwise the round ends like any other and the
+    speculative evaluation is dropped.  Returns (tokens, stats) as ssd()."""
+    P = len(prompt)
+    cache = _prefill(w, cfg, prompt, dtype)
+    blocks = _blocks(gen_len, block)
+    out, forwards, kv_passes = [], 0, 1
+    hist = [0] * (n_draft + 2)
+    mask_id = cfg["mask_id"]
+
+    def n_next_for(rest, has_next):
+        return min(n_draft, len(rest) if has_next else max(len(rest) - 1, 0))
+
+    bi = 0
+    tok, masked, drafts = [mask_id] * blocks[0][1], [True] * blocks[0][1], []
+    while bi < len(blocks):
+        off, Bj = blocks[bi]
+        S = P + off
+        has_next = bi + 1 < len(blocks)
+        nodes = build_chain(tok, masked, drafts)
+        leaf_t, leaf_mk = nodes[-1]
+        leaf_complete = not any(leaf_mk)
+        preds = [_node_forward(w, cfg, nt, S, cache, dtype) if any(mk) else None for (nt, mk) in nodes]
+        leaf_kv = leaf_next = None
+        if leaf_complete:
+            _, leaf_kv = forward_segment(w, cfg, leaf_t, S, cache, dtype, need_logits=False)
+            if has_next:
+                spec = _cache_with(cache, leaf_kv)
+                leaf_next = _node_forward(w, cfg, [mask_id] * blocks[bi + 1][1], S + Bj, spec, dtype)
+        forwards += 1
+        m = 0
+        complete = False
+        while True:
+            if not any(nodes[m][1]):
+                complete = True
+                break
+            p = stepwise_choice(preds[m][2], nodes[m][1])
+            t = int(preds[m][0][p])
+            if m < len(drafts) and (p, t) == (drafts[m][0], int(drafts[m][1])):
+                m += 1
+                continue
+            break
+        if not complete:
+            accepted = [(q, int(d)) for (q, d) in drafts[:m]] + [(p, t)]
+            for (q, d) in accepted:
+                assert masked[q]
+                tok[q], masked[q] = d, False
+            rest = rank_positions(preds[m][2], nodes[m][1], exclude=p)
+            drafts = [(q, int(preds[m][0][q])) for q in rest[:n_next_for(rest, has_next)]]
+            hist[len(accepted)] += 1
+            if trace is not None:
+                trace.append(dict(S=S, accepted=list(accepted), complete=False))
+            if not any(masked):                          # finished the ordinary way
+                _, kv = forward_segment(w, cfg, tok, S, cache, dtype, need_logits=False)
+                cache.append(kv)
+                kv_passes += 1
+                out += tok
+                bi += 1
+                if bi < len(blocks):
+                    tok, masked, drafts = [mask_id] * blocks[bi][1], [True] * blocks[bi][1], []
+            continue
+        # every draft verified and the leaf holds the finished block
+        n_acc = len(drafts)
+        out += leaf_t
+        cache.append(leaf_kv)
+        bi += 1
+        if leaf_next is None:
+            hist[n_acc] += 1
+            if trace is not None:
+                trace.append(dict(S=S, accepted=list(drafts), complete=True))
+            continue
+        Bn = blocks[bi][1]
+        t2, _, c2, _ = leaf_next
+        tok, masked = [mask_id] * Bn, [True] * Bn
+        p2 = stepwise_choice(c2, masked)
+        tok[p2], masked[p2] = int(t2[p2]), False
+        hist[n_acc + 1] += 1
+        if trace is not None:
+            trace.append(dict(S=S, accepted=list(drafts) + [(p2, int(t2[p2]))], complete=True))
+        rest = rank_positions(c2, [True] * Bn, exclude=p2)
+        drafts = [(q, int(t2[q])) for q in rest[:n_next_for(rest, bi + 1 < len(blocks))]]
+        if not any(masked):                              # a one-position block
+            _, kv = forward_segment(w, cfg, tok, P + blocks[bi][0], cache, dtype, need_logits=False)
+            cache.append(kv)
+            kv_passes += 1
+            out += tok
+            bi += 1
+            if bi < len(blocks):
+                tok, masked, drafts = [mask_id] * blocks[bi][1], [True] * blocks[bi][1], []
     return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
 
 

@@ -385,6 +385,47 @@ def test_mix_order_equals_chain_when_every_draft_verifies(tiny):
         assert st["forwards"] == 2 * (1 + math.ceil(31 / (N + 1)))
 
 
+# ----------------------------------------------------------- across the block boundary
+@pytest.mark.parametrize("seed,gen_len,block", [(1001, 64, 32), (8, 40, 8), (7, 50, 16)])
+def test_cross_block_round_is_lossless_and_saves_forwards(tiny, seed, gen_len, block):
+    """Section 3.2.2: once fewer than N positions remain, candidates come from the next block.  The
+    oracle's restricted form (the leaf holds the finished block and predicts the next one) keeps the
+    output identical to stepwise decoding and never needs more forwards than the in-block chain."""
+    cfg, w = tiny
+    prompt = synth.gen_prompt(cfg, seed, 48)
+    ref, _ = decode.stepwise(w, cfg, prompt, gen_len, block)
+    for N in (1, 2, 4, 8):
+        out, st = decode.ssd_cross_block(w, cfg, prompt, gen_len, block, N)
+        _, sr = decode.ssd(w, cfg, prompt, gen_len, block, N)
+        assert out == ref, f"N={N}"
+        hist = st["accept_hist"]
+        assert hist[0] == 0 and sum(a * h for a, h in enumerate(hist)) == gen_len
+        assert all(h == 0 for a, h in enumerate(hist) if a > N + 1)
+        assert st["forwards"] <= sr["forwards"]
+        assert 1.0 - st["forwards"] / gen_len <= N / (N + 1) + 1e-12          # Section 5.1's bound still holds
+    out0, st0 = decode.ssd_cross_block(w, cfg, prompt, gen_len, block, 0)
+    assert out0 == ref and st0["forwards"] == gen_len                          # no drafts: stepwise
+
+
+@pytest.mark.parametrize("N", [3, 4])
+def test_cross_block_closed_form_with_zero_attention(tiny, N):
+    """Every draft verifies (zero attention output projections, left-to-right order): each block
+    boundary that has a next block costs no forward of its own, so B = 32 takes
+    1 + n_blocks * ceil((B - 1) / (N + 1)) forwards instead of n_blocks * (1 + ceil((B - 1) / (N + 1)))."""
+    cfg, w0 = tiny
+    w = dict(w0)
+    w["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w0["layers"]]
+    prompt = synth.gen_prompt(cfg, 3, 20)
+    trace = []
+    out, st = decode.ssd_cross_block(w, cfg, prompt, 96, 32, N, trace=trace)
+    per_block = math.ceil(31 / (N + 1))
+    assert st["forwards"] == 1 + 3 * per_block
+    assert decode.ssd(w, cfg, prompt, 96, 32, N)[1]["forwards"] == 3 * (1 + per_block)
+    assert out == decode.stepwise(w, cfg, prompt, 96, 32)[0]
+    assert st["kv_passes"] == 2              # the prompt and the last block: the others keep their leaf's KV
+    assert sum(r["complete"] for r in trace) == 2
+
+
 def test_build_chain_nodes():
     """Section 3.2.3: exactly N+1 nodes; node i holds the first i drafts."""
     nodes = decode.build_chain([9, 9, 9, 1], [True, True, True, False], [(2, 5), (0, 6)])

@@ -83,7 +83,7 @@ def main():
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         eng = binding.SSD(cfg, wg, max_seqs=nseq, max_seq_len=P + G, block=B, max_draft=N,
-                          max_rows=max(P, S, nseq * max(N + 1, 2 * N) * B))
+                          max_rows=max(P, S, nseq * max(N + 2, 2 * N) * B))
         # ---- verification forward at prefix S, fixed block state with N drafts, every sequence of the batch
         note(f"context created; prefill of {nseq} x {S} positions")
         for i in range(nseq):
@@ -195,7 +195,11 @@ def main():
             eng.set_tree_mode(1)                                 # the mix-order tree (Section 5.2), for context
             toks_mix, st_mix = eng.generate(prompts, G, B, N)
             eng.set_tree_mode(0)
-            same = bool(np.array_equal(toks_ssd, toks_step) and np.array_equal(toks_mix, toks_step))
+            eng.set_cross_block(1)                               # rounds that reach across the block boundary (Section 3.2.2)
+            toks_x, st_x = eng.generate(prompts, G, B, N)
+            eng.set_cross_block(0)
+            same = bool(np.array_equal(toks_ssd, toks_step) and np.array_equal(toks_mix, toks_step) and
+                        np.array_equal(toks_x, toks_step))
             GT = G * nseq                                        # tokens generated over the whole batch
             gen = dict(
                 ssd_tokens_per_s=GT / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_step["total_ms"] / 1e3),
@@ -205,7 +209,9 @@ def main():
                 stepwise_ms_per_forward=st_step["decode_ms"] / st_step["forwards"],
                 ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"],
                 mix_order_tokens_per_s=GT / (st_mix["total_ms"] / 1e3), mix_order_forwards=st_mix["forwards"],
-                mix_order_accept_hist=st_mix["accept_hist"][:N + 2])
+                mix_order_accept_hist=st_mix["accept_hist"][:N + 2],
+                cross_block_tokens_per_s=GT / (st_x["total_ms"] / 1e3), cross_block_forwards=st_x["forwards"],
+                cross_block_kv_passes=st_x["kv_passes"])
 
     # ---- roofline arithmetic
     M = nseq * (N + 1) * B

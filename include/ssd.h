@@ -203,6 +203,17 @@ int ssd_set_kernel_path(ssd_ctx* ctx, int path);
  * previous value or an error. */
 int ssd_set_boundary_fusion(ssd_ctx* ctx, int on);
 
+/* A round across the block boundary in ssd_generate (Section 3.2.2: once fewer than N positions
+ * remain in the current block, candidates come from the next block).  1 = while a next block
+ * exists the drafts may cover every remaining position of the current block; the chain's leaf
+ * then holds the finished block, and the same forward runs the next block, all masked, behind it.
+ * If every draft verifies, the block is finished, its KV stays in the cache, and the next block
+ * starts with one token and its drafts: the boundary costs no forward of its own.  Otherwise the
+ * round ends like any other.  Needs max_rows >= (draft_depth + 2) * block rows per sequence to
+ * take effect; greedy chain only.  The generated tokens are the same.  Default 0.  Returns the
+ * previous value or an error. */
+int ssd_set_cross_block(ssd_ctx* ctx, int on);
+
 /* Shape of the verification tree of ssd_verify_tree / ssd_generate:
  * 0 = the greedy chain of n_draft + 1 nodes (Section 3.2.3), 1 = the mix-order
  * tree (Section 5.2, Table 3): the chain plus, for every chain node but the last

@@ -493,11 +493,12 @@ __global__ __launch_bounds__(256) void k_lm_merge(const float* __restrict__ part
 __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
                                                const float* __restrict__ row_conf, const int* __restrict__ row_arg,
                                                const float* __restrict__ row_max, StepResult* __restrict__ result,
-                                               int blockB, int maxDraft, int mask_id) {
+                                               int* __restrict__ out_tok, int max_seq_len, int blockB, int maxDraft,
+                                               int mask_id) {
     const int gi = blockIdx.x, lane = threadIdx.x;
     const GroupDesc g = fw->groups[gi];
     const ssd_step_out out = fw->out;
-    if (g.mode != GM_DECODE) return;
+    if (g.mode != GM_DECODE || g.spec_of1 != 0) return;   // a speculative group is its master's business
     SeqState* s = &state[g.seq];
     const int nd = g.n_chain - 1;                         // drafts = chain nodes - 1
     const int blen = g.blen;
@@ -539,7 +540,9 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         tstar = row_arg[g.row0 + node * blen + pstar];
     };
     int m = 0;
+    bool complete = false;
     while (true) {
+        if (cur == 0ull) { complete = true; break; }     // the drafts covered every masked position: the leaf
         choose(m);
         const int dp = __shfl(my_dpos, m, 64), dt = __shfl(my_dtok, m, 64);
         if (m < nd && pstar == dp && tstar == dt) {
@@ -548,6 +551,83 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
             continue;
         }
         break;
+    }
+    StepResult* r = &result[g.seq];
+    if (complete) {
+        // Every draft verified and the block is finished (Section 3.2.2, the round across the block
+        // boundary).  Its tokens go to the output; its KV was written by the leaf in this forward.
+        // The group behind the leaf, if any, is the next block's block-start forward: its stepwise
+        // choice is one more accepted token and its other positions give the next drafts.
+        if (lane < m) {
+            r->acc_pos[lane] = my_dpos;
+            r->acc_tok[lane] = my_dtok;
+            s->tok[my_dpos] = my_dtok;
+            if (out.acc_pos) out.acc_pos[(size_t)gi * (maxDraft + 1) + lane] = my_dpos;
+            if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + lane] = my_dtok;
+        }
+        __syncthreads();
+        if (g.out_off >= 0 && lane < blen) out_tok[(size_t)g.seq * max_seq_len + g.out_off + lane] = s->tok[lane];
+        __syncthreads();
+        int n_acc = m, n_next = 0;
+        unsigned long long rem = 0ull;
+        if (g.spec_next1 != 0) {
+            const GroupDesc g2 = fw->groups[g.spec_next1 - 1];
+            const int blen2 = g2.blen;
+            cur = blen2 >= 64 ? ~0ull : ((1ull << blen2) - 1ull);
+            {   // stepwise choice of the next block's all-masked node
+                const int row = g2.row0 + lane;
+                const bool valid = lane < blen2;
+                c = valid ? row_conf[row] : -1.f;
+                float bc = c;
+                int bp = lane;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    const float oc = __shfl_xor(bc, off, 64);
+                    const int op = __shfl_xor(bp, off, 64);
+                    if (oc > bc || (oc == bc && op < bp)) { bc = oc; bp = op; }
+                }
+                pstar = bp;
+                tstar = row_arg[g2.row0 + pstar];
+            }
+            rem = cur & ~(1ull << pstar);
+            const int n_rem = __popcll(rem);
+            n_next = min(g2.n_draft_next, g2.allow_full ? n_rem : max(n_rem - 1, 0));
+            const bool mine = (rem >> lane) & 1ull;
+            int rank = 0;
+            for (int qd = 0; qd < 64; ++qd) {
+                const float cq = __shfl(c, qd, 64);
+                if (((rem >> qd) & 1ull) && (cq > c || (cq == c && qd < lane))) ++rank;
+            }
+            const int my_tok = row_arg[g2.row0 + (lane < blen2 ? lane : 0)];
+            if (mine && rank < n_next) {
+                r->next_pos[rank] = lane;
+                r->next_tok[rank] = my_tok;
+                s->draft_pos[rank] = lane;
+                s->draft_tok[rank] = my_tok;
+                if (out.next_pos) out.next_pos[(size_t)gi * maxDraft + rank] = lane;
+                if (out.next_tok) out.next_tok[(size_t)gi * maxDraft + rank] = my_tok;
+            }
+            s->tok[lane] = mask_id;
+            __syncthreads();
+            if (lane == 0) {
+                s->tok[pstar] = tstar;
+                r->acc_pos[m] = pstar;
+                r->acc_tok[m] = tstar;
+                if (out.acc_pos) out.acc_pos[(size_t)gi * (maxDraft + 1) + m] = pstar;
+                if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + m] = tstar;
+            }
+            n_acc = m + 1;
+        }
+        if (lane == 0) {
+            r->n_accept = n_acc;
+            r->n_next = n_next;
+            r->completed = 1;
+            s->masked = rem;
+            s->n_draft = n_next;
+            if (out.n_accept) out.n_accept[gi] = n_acc;
+            if (out.n_next) out.n_next[gi] = n_next;
+        }
+        return;
     }
     // mix order (Section 5.2): the choice is the draft after the expected one -> accept it and take
     // one more token from the node that holds drafts 1..m and m+2; that node has no children
@@ -565,7 +645,8 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     const int n_acc = m + 1 + (res_pos >= 0 ? 1 : 0);
     const unsigned long long rem = cur & ~(1ull << pstar);
     const int n_rem = __popcll(rem);
-    const int n_next = min(g.n_draft_next, max(n_rem - 1, 0));
+    // the leaf keeps one masked position to predict, unless a next block exists for it to reach into
+    const int n_next = min(g.n_draft_next, g.allow_full ? n_rem : max(n_rem - 1, 0));
     const bool mine = (rem >> lane) & 1ull;
     int rank = 0;
     for (int qd = 0; qd < 64; ++qd) {
@@ -573,7 +654,6 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         if (((rem >> qd) & 1ull) && (cq > c || (cq == c && qd < lane))) ++rank;
     }
     const int my_tok = row_arg[g.row0 + last * blen + (lane < blen ? lane : 0)];
-    StepResult* r = &result[g.seq];
     if (mine && rank < n_next) {
         r->next_pos[rank] = lane;
         r->next_tok[rank] = my_tok;
@@ -597,6 +677,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     if (lane == 0) {
         r->n_accept = n_acc;
         r->n_next = n_next;
+        r->completed = 0;
         s->masked = rem;
         s->n_draft = n_next;
         if (out.n_accept) out.n_accept[gi] = n_acc;
@@ -691,7 +772,7 @@ void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
 
 void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st) {
     k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result,
-                                      c->dm.block, c->dm.max_draft, c->dm.mask_id);
+                                      c->b.out_tok, c->dm.max_seq_len, c->dm.block, c->dm.max_draft, c->dm.mask_id);
 }
 
 // Helpers of the kernel-level entry points.

@@ -187,6 +187,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->kernel_path = 1;
     c->fuse_boundary = 1;
     c->tree_mode = 0;
+    c->cross_block = 0;
     c->use_graphs = 0;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
@@ -271,6 +272,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_boundary_fusion(ss
     if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
     const int old = c->fuse_boundary;
     c->fuse_boundary = on;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_cross_block(ssd_ctx* c, int on) {
+    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
+    const int old = c->cross_block;
+    c->cross_block = on;
     return old;
 }
 
@@ -510,18 +518,19 @@ static int mix_nodes(const ssd_ctx* c, int n_draft) { return c->tree_mode == 1 &
 // Appends a group to a header: n_chain chain nodes (node j holds drafts 1..j), then n_extra mix-order
 // nodes (node m holds drafts 1..m and m+2); returns the rows it takes.
 static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_chain, int n_extra, int n_draft_next,
-                     int fresh, int raw_off, int out_off) {
+                     int fresh, int raw_off, int out_off, int allow_full = 0, bool leaf_writes_kv = false) {
     GroupDesc& g = hd.groups[hd.n_groups];
     const int n_nodes = n_chain + n_extra;
     g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
     g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.n_chain = n_chain;
+    g.spec_next1 = 0; g.spec_of1 = 0; g.allow_full = allow_full; g.pad = 0;
     int vrows = hd.n_nodes ? hd.nodes[hd.n_nodes - 1].vrow0 + ((hd.nodes[hd.n_nodes - 1].blen + 63) & ~63) : 0;
     for (int j = 0; j < n_nodes; ++j) {
         NodeDesc& nd = hd.nodes[hd.n_nodes++];
         nd.seq = seq; nd.row0 = hd.M + j * blen; nd.blen = blen; nd.S = S; nd.group = hd.n_groups;
         nd.j = j < n_chain ? j : j - n_chain;
         nd.extra = j < n_chain ? -1 : j - n_chain + 1;
-        nd.write_kv = mode != GM_DECODE;
+        nd.write_kv = mode != GM_DECODE || (leaf_writes_kv && j == n_chain - 1);
         nd.vrow0 = vrows;
         vrows += (blen + 63) & ~63;
     }
@@ -678,8 +687,9 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
         // reach the cache in each layer's rotary kernel, before that layer's attention kernel, so the
         // next block's node simply reads a prefix that is one block longer.  Fused only while the
         // forward still fits max_rows.
-        bool fuse[SSD_MAX_SEQS] = {};
-        if (c->fuse_boundary) {
+        bool fuse[SSD_MAX_SEQS] = {}, reach[SSD_MAX_SEQS] = {};
+        const bool cross = c->cross_block && c->tree_mode == 0;
+        {
             int rows = 0;
             for (int i = 0; i < n; ++i) {
                 if (phase[i] == DONE) continue;
@@ -687,26 +697,53 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
                 const int ndr = phase[i] == FRESH ? 0 : n_dr[i];
                 rows += phase[i] == APPEND ? bl : (ndr + 1 + mix_nodes(c, ndr)) * bl;
             }
+            // extra rows, granted while the forward still fits max_rows: the next block behind a leaf that
+            // holds a finished block (see below), then the next block's draft next to a KV append
             for (int i = 0; i < n; ++i) {
+                if (!cross || phase[i] != DECODE || blk[i] + 1 >= n_blocks || n_dr[i] != n_masked[i]) continue;
+                const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
+                if (rows + bln <= d.max_rows) { reach[i] = true; rows += bln; }
+            }
+            for (int i = 0; c->fuse_boundary && i < n; ++i) {
                 if (phase[i] != APPEND || blk[i] + 1 >= n_blocks) continue;
                 const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
                 if (rows + bln <= d.max_rows) { fuse[i] = true; rows += bln; }
             }
         }
+        // A round across the block boundary (Section 3.2.2): while a next block exists the drafts may
+        // cover every masked position of the current block (allow_full); when they do, the chain's leaf
+        // holds the finished block, writes its KV, and a group for the next block, all masked, runs behind
+        // it in the same forward.  The acceptance kernel uses that group only if every draft verifies.
+        int spec_master[SSD_MAX_SEQS];
+        for (int i = 0; i < n; ++i) spec_master[i] = -1;
         for (int pass = 0; pass < 2; ++pass)          // decode groups first, then KV appends
             for (int i = 0; i < n; ++i) {
                 if (phase[i] == DONE) continue;
                 const int bl = std::min(block, gen_len - blk[i] * block);
+                const bool has_next = blk[i] + 1 < n_blocks;
                 if (pass == 0 && phase[i] != APPEND) {
                     if (phase[i] == FRESH) { n_masked[i] = bl; n_dr[i] = 0; }
-                    add_group(hd, i, GM_DECODE, bl, c->cached_len[i], n_dr[i] + 1, mix_nodes(c, n_dr[i]), draft_depth,
-                              phase[i] == FRESH, 0, -1);
+                    int ndr = n_dr[i];
+                    const int bln = has_next ? std::min(block, gen_len - (blk[i] + 1) * block) : 0;
+                    if (!reach[i] && ndr >= n_masked[i]) ndr = n_masked[i] - 1;   // the leaf must keep a position to predict
+                    const int master = hd.n_groups;
+                    add_group(hd, i, GM_DECODE, bl, c->cached_len[i], ndr + 1, mix_nodes(c, ndr), draft_depth,
+                              phase[i] == FRESH, 0, reach[i] ? blk[i] * block : -1, cross && has_next, reach[i]);
+                    if (reach[i]) {
+                        const bool next_has_next = blk[i] + 2 < n_blocks;
+                        hd.groups[master].spec_next1 = hd.n_groups + 1;
+                        add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, 0, draft_depth, 1, 0, -1,
+                                  cross && next_has_next);
+                        hd.groups[hd.n_groups - 1].spec_of1 = master + 1;
+                        spec_master[i] = master;
+                    }
                     any_decode = true;
                 } else if (pass == 0 && fuse[i]) {
                     const int bln = std::min(block, gen_len - (blk[i] + 1) * block);
                     n_masked[i] = bln;
                     n_dr[i] = 0;
-                    add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, 0, draft_depth, 1, 0, -1);
+                    const bool next_has_next = blk[i] + 2 < n_blocks;
+                    add_group(hd, i, GM_DECODE, bln, c->cached_len[i] + bl, 1, 0, draft_depth, 1, 0, -1, cross && next_has_next);
                     any_decode = true;
                 } else if (pass == 1 && phase[i] == APPEND) {
                     add_group(hd, i, GM_APPEND, bl, c->cached_len[i], 1, 0, 0, 0, 0, blk[i] * block);
@@ -724,8 +761,27 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
         for (int gi = 0; gi < hd.n_groups; ++gi) {
             const GroupDesc& g = hd.groups[gi];
             const int i = g.seq;
+            if (g.mode == GM_DECODE && g.spec_of1 != 0) continue;     // reported through its master group
             if (g.mode == GM_DECODE) {
                 const StepResult& r = c->host_result[i];
+                if (r.completed) {
+                    // the round verified drafts for every masked position: the block is finished, its tokens
+                    // are in the output and its KV in the cache; the next block has its first token already
+                    const int got_next = g.spec_next1 != 0 ? 1 : 0;
+                    if (spec_master[i] != gi || r.n_accept != n_masked[i] + got_next) {
+                        set_err(c, "generate: acceptance kernel finished a block with %d tokens, %d were masked", r.n_accept, n_masked[i]);
+                        return done(SSD_EHIP);
+                    }
+                    sta.accept_hist[r.n_accept]++;
+                    sta.tokens += r.n_accept;
+                    c->cached_len[i] += g.blen;
+                    blk[i]++;
+                    if (blk[i] == n_blocks) { phase[i] = DONE; live--; continue; }
+                    n_masked[i] = std::min(block, gen_len - blk[i] * block) - 1;
+                    n_dr[i] = r.n_next;
+                    phase[i] = n_masked[i] == 0 ? APPEND : DECODE;
+                    continue;
+                }
                 if (r.n_accept < 1 || r.n_accept > g.n_chain || r.n_accept > n_masked[i]) {
                     set_err(c, "generate: acceptance kernel returned %d for a chain of %d nodes", r.n_accept, g.n_chain);
                     return done(SSD_EHIP);

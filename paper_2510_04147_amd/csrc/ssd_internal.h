@@ -27,6 +27,13 @@ struct GroupDesc {
     int out_off;    // GM_APPEND: offset into the device token output, or -1
     int node0;      // index of the group's first node
     int n_chain;    // GM_DECODE: nodes 0 .. n_chain-1 are the chain, the rest mix-order nodes
+    // A round that reaches across the block boundary (Section 3.2.2): the chain's drafts cover every
+    // masked position, so its leaf holds the finished block (and writes its KV); group spec_next1 - 1
+    // evaluates the next block behind that leaf.  0 = none.  The speculative group has spec_of1 =
+    // its master's index + 1 and is handled by the master's work-group of the acceptance kernel.
+    int spec_next1, spec_of1;
+    int allow_full; // next drafts may cover every remaining masked position (a next block exists)
+    int pad;
 };
 
 struct NodeDesc {
@@ -59,6 +66,8 @@ struct SeqState {
 // by ssd_generate.
 struct StepResult {
     int n_accept, n_next;
+    int completed;  // the round verified drafts for every masked position: the block is finished and its KV cached
+    int pad;
     int acc_pos[SSD_MAX_DRAFT + 1], acc_tok[SSD_MAX_DRAFT + 1];
     int next_pos[SSD_MAX_DRAFT + 1], next_tok[SSD_MAX_DRAFT + 1];
 };
@@ -165,6 +174,7 @@ struct ssd_ctx {
     int kernel_path;
     int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
     int tree_mode;       // 0 = greedy chain (Section 3.2.3), 1 = mix-order tree (Section 5.2)
+    int cross_block;     // ssd_generate: the last round of a block may reach into the next block (Section 3.2.2)
     // HIP graphs of the forward's kernel sequence, one per launch shape.  Everything that changes
     // between forwards of one shape (tokens, prefix lengths, drafts, output pointers) lives in
     // device memory, so a shape's second forward is captured and later ones replay the graph.

@@ -133,6 +133,17 @@ def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
         eng.set_tree_mode(0)
     assert np.array_equal(out, base), "mix order"
     print(f"mix order N=4: forwards {st['forwards']} accept_hist {st['accept_hist'][:6]}")
+    # a round across the block boundary (MFMA path, leaf writes KV, next block behind it): same tokens
+    eng.set_cross_block(1)
+    try:
+        out, st = eng.generate([prompt], 64, 32, 4)
+        out8, st8 = eng.generate([prompt], 64, 8, 4)
+    finally:
+        eng.set_cross_block(0)
+    assert np.array_equal(out, base), "cross block"
+    base8, s8 = eng.generate([prompt], 64, 8, 4)
+    assert np.array_equal(out8, base8) and st8["forwards"] <= s8["forwards"]
+    print(f"cross block: block 32 forwards {st['forwards']}; block 8 forwards {st8['forwards']} vs {s8['forwards']}")
     # two sequences at once, different prompt lengths
     p2 = synth.gen_prompt(cfg, 77, 61)
     solo, _ = eng.generate([p2], 64, 32, 0)

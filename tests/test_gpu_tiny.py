@@ -243,6 +243,53 @@ def test_zero_attention_closed_form_on_gpu(setup):
     eng.close()
 
 
+def test_round_across_the_block_boundary(setup):
+    """Section 3.2.2 (ssd_set_cross_block): drafts may cover the whole rest of a block, the leaf then
+    holds the finished block and the next block is evaluated behind it in the same forward.  Tokens
+    stay those of stepwise decoding; rounds, forwards and KV passes agree with the oracle's
+    ssd_cross_block; with zero attention output projections every boundary is free (closed form)."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=32, max_draft=8, max_rows=2 * 10 * 32)
+    try:
+        assert eng.set_cross_block(1) == 0
+        for seed, gen, blk in ((1001, 64, 32), (8, 40, 8), (7, 50, 16)):
+            prompt = synth.gen_prompt(cfg, seed, 48)
+            base, _ = eng.generate([prompt], gen, blk, 0)
+            for N in (1, 2, 4, 8):
+                out, st = eng.generate([prompt], gen, blk, N)
+                assert np.array_equal(out, base), (seed, N)
+                ref, so = decode.ssd_cross_block(w, cfg, prompt, gen, blk, N)
+                if list(base[0]) == ref:                   # no near-tie anywhere: the rounds must agree too
+                    assert st["forwards"] == so["forwards"], (seed, N, st, so)
+                    assert st["accept_hist"][:N + 2] == so["accept_hist"][:N + 2], (seed, N)
+                assert st["tokens"] == gen
+        # two sequences of different lengths in one batch, boundaries at different forwards
+        p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)
+        both, st = eng.generate([p0, p1], 40, 8, 3)
+        eng.set_cross_block(0)
+        a, _ = eng.generate([p0], 40, 8, 0)
+        b, _ = eng.generate([p1], 40, 8, 0)
+        assert np.array_equal(both[0], a[0]) and np.array_equal(both[1], b[0]) and st["tokens"] == 80
+    finally:
+        eng.close()
+    w0 = dict(w)
+    w0["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w["layers"]]
+    eng = binding.SSD(cfg, synth.weights_to(w0, "cuda"), max_seqs=1, max_seq_len=256, block=32, max_draft=8,
+                      max_rows=10 * 32)
+    try:
+        eng.set_cross_block(1)
+        prompt = synth.gen_prompt(cfg, 3, 20)
+        ref, _ = decode.stepwise(w0, cfg, prompt, 96, 32)
+        for N in (3, 4):
+            out, st = eng.generate([prompt], 96, 32, N)
+            assert list(out[0]) == ref
+            assert st["forwards"] == 1 + 3 * math.ceil(31 / (N + 1)), (N, st)
+            assert st["kv_passes"] == 2                    # the prompt and the last block
+    finally:
+        eng.close()
+
+
 def test_repeated_forward_is_bit_identical_and_node_independent(setup):
     cfg, w, wg, eng = setup
     prompt = synth.gen_prompt(cfg, 5, 40)

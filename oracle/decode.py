@@ -24,6 +24,17 @@
                supplies one more token.  Extra nodes have no children: 2N nodes
                for N drafts (the table's batch sizes 6 / 8 / 10).
 
+  dual cache   stepwise_dual / ssd_dual / bruteforce_full: the cache of the paper's
+               experiments (Section 4.1: prefix and suffix cache, refreshed every
+               fixed number of decoded tokens).  A refresh is one forward over the
+               whole sequence, prompt, decoded tokens and every still masked
+               position, with full bidirectional attention; it renews the keys and
+               values of all positions and is itself the decoding step of that
+               moment.  Between refreshes only the current block is computed, against
+               the cached keys and values of all other positions.  A chain never
+               reaches past the next refresh, so SSD and stepwise decoding refresh
+               at the same states and stay identical.
+
 Readings where the paper is silent (all also applied by the HIP path):
   * confidence c = softmax probability of the arg-max token (Section 3.2.2);
   * the mask token can never be predicted (excluded from max / arg-max / sum);
@@ -42,7 +53,7 @@ import math
 
 import torch
 
-from .model import KVCache, forward_full_blockcausal, forward_segment
+from .model import KVCache, forward_block_dual, forward_full_blockcausal, forward_segment
 
 
 # --------------------------------------------------------------------------
@@ -352,6 +363,106 @@ def ssd_cross_block(w, cfg, prompt, gen_len, block, n_draft, dtype=torch.float64
             if bi < len(blocks):
                 tok, masked, drafts = [mask_id] * blocks[bi][1], [True] * blocks[bi][1], []
     return out, dict(forwards=forwards, kv_passes=kv_passes, accept_hist=hist)
+
+
+# --------------------------------------------------------------------------
+# the dual cache with periodic refresh (Section 4.1)
+# --------------------------------------------------------------------------
+def _refresh(w, cfg, x, dtype):
+    """One forward over the whole sequence x, every position attending to every position.
+    Returns (logits [T, V], keys per layer, values per layer)."""
+    logits, kv = forward_segment(w, cfg, x, 0, KVCache(cfg["n_layers"]), dtype)
+    return logits, [k for (k, _) in kv], [v for (_, v) in kv]
+
+
+def stepwise_dual(w, cfg, prompt, gen_len, block, refresh, dtype=torch.float64):
+    """Greedy stepwise decoding with the dual cache: the cache is refreshed at the start and
+    whenever `refresh` tokens have been decoded since the last refresh.  Returns (tokens, stats)."""
+    P = len(prompt)
+    x = list(prompt) + [cfg["mask_id"]] * gen_len
+    forwards = refreshes = 0
+    since = None
+    K = V = None
+    for (off, Bj) in _blocks(gen_len, block):
+        S = P + off
+        masked = [True] * Bj
+        while any(masked):
+            if since is None or since >= refresh:
+                logits, K, V = _refresh(w, cfg, x, dtype)
+                logits = logits[S:S + Bj]
+                refreshes += 1
+                since = 0
+            else:
+                logits = forward_block_dual(w, cfg, x[S:S + Bj], S, K, V, dtype)
+            forwards += 1
+            t, _, c, _ = predict(logits, cfg["mask_id"])
+            p = stepwise_choice(c, masked)
+            x[S + p], masked[p] = int(t[p]), False
+            since += 1
+    return x[P:], dict(forwards=forwards, refreshes=refreshes)
+
+
+def ssd_dual(w, cfg, prompt, gen_len, block, n_draft, refresh, dtype=torch.float64, trace=None, max_forwards=None):
+    """SSD (greedy chain) with the dual cache.  A refresh forward holds the one current state (no
+    chain) and supplies the next round's drafts, as a block's first forward does; a chain carries
+    at most refresh - since - 1 drafts, so that no round decodes past the next refresh."""
+    P = len(prompt)
+    x = list(prompt) + [cfg["mask_id"]] * gen_len
+    forwards = refreshes = 0
+    hist = [0] * (n_draft + 2)
+    since = None
+    K = V = None
+    for (off, Bj) in _blocks(gen_len, block):
+        S = P + off
+        tok, masked = [cfg["mask_id"]] * Bj, [True] * Bj
+        drafts = []
+        while any(masked):
+            if max_forwards is not None and forwards >= max_forwards:
+                return x[P:], dict(forwards=forwards, refreshes=refreshes, accept_hist=hist)
+            is_refresh = since is None or since >= refresh
+            if is_refresh:
+                drafts = []
+                logits, K, V = _refresh(w, cfg, x, dtype)
+                preds = [predict(logits[S:S + Bj], cfg["mask_id"])]
+                nodes = [(list(tok), list(masked))]
+                refreshes += 1
+                since = 0
+            else:
+                drafts = drafts[:max(0, min(len(drafts), sum(masked) - 1, refresh - since - 1))]
+                nodes = build_chain(tok, masked, drafts)
+                preds = [predict(forward_block_dual(w, cfg, nt, S, K, V, dtype), cfg["mask_id"]) for (nt, _) in nodes]
+            forwards += 1
+            accepted, next_drafts, m = accept_chain([p[0] for p in preds], [p[2] for p in preds],
+                                                    [nm for (_, nm) in nodes], drafts, n_draft)
+            if trace is not None:
+                trace.append(dict(S=S, tok=list(tok), masked=list(masked), drafts=list(drafts), refresh=is_refresh,
+                                  x=list(x), t=[p[0] for p in preds], m=[p[1] for p in preds],
+                                  c=[p[2] for p in preds], margin=[p[3] for p in preds],
+                                  accepted=list(accepted), next_drafts=list(next_drafts)))
+            hist[len(accepted)] += 1
+            for (q, d) in accepted:
+                assert masked[q]
+                tok[q], masked[q] = d, False
+                x[S + q] = d
+            since += len(accepted)
+            drafts = next_drafts
+    return x[P:], dict(forwards=forwards, refreshes=refreshes, accept_hist=hist)
+
+
+def bruteforce_full(w, cfg, prompt, gen_len, block, dtype=torch.float64):
+    """Stepwise decoding in block order with no cache at all and full bidirectional attention: every
+    step recomputes the whole sequence, masked future blocks included."""
+    P = len(prompt)
+    x = list(prompt) + [cfg["mask_id"]] * gen_len
+    everyone = [0] * len(x)
+    for (off, Bj) in _blocks(gen_len, block):
+        masked = [True] * Bj
+        while any(masked):
+            logits = forward_full_blockcausal(w, cfg, x, everyone, dtype)
+            t, _, c, _ = predict(logits[P + off: P + off + Bj], cfg["mask_id"])
+            p = stepwise_choice(c, masked)
+            x[P + off + p], masked[p] = int(t[p]), False
+    return x[P:]
 
 
 def bruteforce(w, cfg, prompt, gen_len, block, dtype=torch.float64):

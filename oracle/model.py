@@ -139,6 +139,23 @@ def forward_segment(w, cfg, tokens, pos0, cache, dtype=torch.float64, need_logit
     return hn @ w["lm_head"].to(dtype).T, new_kv
 
 
+def forward_block_dual(w, cfg, tokens, pos0, k_all, v_all, dtype=torch.float64):
+    """Dual (prefix + suffix) cache of the paper's experimental setup (Section 4.1): the rows of the
+    current block, at positions pos0.., attend to their own freshly computed keys and values and to
+    the CACHED keys and values of every other position of the sequence, before the block and after
+    it.  k_all[l], v_all[l]: [T, Hkv, dh] of the last refresh.  Returns logits [n, V]."""
+    tokens = torch.as_tensor(tokens, dtype=torch.long)
+    n = tokens.shape[0]
+    pos = pos0 + torch.arange(n)
+    h = w["embed"][tokens].to(dtype)
+    for l, lw in enumerate(w["layers"]):
+        k_other = torch.cat([k_all[l][:pos0], k_all[l][pos0 + n:]], 0)
+        v_other = torch.cat([v_all[l][:pos0], v_all[l][pos0 + n:]], 0)
+        h, _, _ = _layer(h, lw, cfg, pos, k_other, v_other, None, dtype)
+    hn = _operand(rms_norm(h, w["final_norm"], cfg["rms_eps"]), cfg)
+    return hn @ w["lm_head"].to(dtype).T
+
+
 def forward_full_blockcausal(w, cfg, tokens, seg, dtype=torch.float64):
     """Cache-free evaluation of a whole sequence: position i may attend to
     position j iff seg[j] <= seg[i].  Returns logits [len, V]."""

@@ -447,3 +447,83 @@ def test_semi_autoregressive_order(tiny):
         assert all(0 <= p < 8 for p, _ in rec["accepted"])
         assert 1 <= len(rec["accepted"]) <= len(rec["drafts"]) + 1
         assert len(rec["t"]) == len(rec["drafts"]) + 1      # N_eff + 1 nodes
+
+
+# ------------------------------------------------- dual cache with periodic refresh (Section 4.1)
+def test_dual_cache_refreshed_every_token_is_cache_free_decoding():
+    """With a refresh before every token nothing cached is ever used: decoding must equal the
+    cache-free run that recomputes the whole sequence, future masked blocks included, with full
+    bidirectional attention for every token (a separate evaluation path: explicit all-true mask)."""
+    cfg = small_cfg()
+    w = synth.gen_weights(cfg, 3, std=0.2)
+    prompt = synth.gen_prompt(cfg, 5, 11)
+    out, st = decode.stepwise_dual(w, cfg, prompt, 20, 8, refresh=1)
+    assert st["refreshes"] == st["forwards"] == 20
+    assert out == decode.bruteforce_full(w, cfg, prompt, 20, 8)
+    # ... and the future blocks do matter: the block-causal decoding of the same model differs
+    assert out != decode.stepwise(w, cfg, prompt, 20, 8)[0]
+
+
+def test_dual_cache_block_forward_right_after_a_refresh_reproduces_it():
+    """The keys and values a refresh caches are those of the state it ran on, so computing any block
+    of that state against the cache (prefix before it, suffix behind it) must give the refresh's own
+    logits for that block.  A suffix or prefix taken at the wrong positions fails this."""
+    cfg = small_cfg()
+    w = synth.gen_weights(cfg, 4, std=0.2)
+    x = list(synth.gen_prompt(cfg, 6, 13)) + [cfg["mask_id"]] * 7 + list(synth.gen_prompt(cfg, 7, 5)) + [cfg["mask_id"]] * 9
+    logits, K, V = decode._refresh(w, cfg, x, torch.float64)
+    for (pos0, n) in ((13, 7), (0, 13), (20, 5), (25, 9), (3, 30)):
+        got = model.forward_block_dual(w, cfg, x[pos0:pos0 + n], pos0, K, V)
+        assert torch.allclose(got, logits[pos0:pos0 + n], rtol=0, atol=1e-10), (pos0, n)
+    # the suffix is really read: without it the logits change
+    Kc = [k[:20] for k in K]
+    Vc = [v[:20] for v in V]
+    cut = model.forward_block_dual(w, cfg, x[13:20], 13, Kc, Vc)
+    assert (cut - logits[13:20]).abs().max() > 1e-6
+
+
+@pytest.mark.parametrize("refresh", [1, 3, 8, 11, 1000])
+def test_ssd_with_dual_cache_is_token_identical_to_stepwise(tiny, refresh):
+    """Losslessness does not depend on the cache: with the refresh schedule of Section 4.1 (every
+    `refresh` decoded tokens) SSD refreshes at the same states as stepwise decoding."""
+    cfg, w = tiny
+    prompt = synth.gen_prompt(cfg, 21, 30)
+    gen_len, block = 40, 8
+    ref, sref = decode.stepwise_dual(w, cfg, prompt, gen_len, block, refresh)
+    assert sref["forwards"] == gen_len and sref["refreshes"] == math.ceil(gen_len / min(refresh, gen_len))
+    for N in (0, 1, 3, 5):
+        out, st = decode.ssd_dual(w, cfg, prompt, gen_len, block, N, refresh)
+        assert out == ref, (N, refresh)
+        assert st["refreshes"] == sref["refreshes"]
+        hist = st["accept_hist"]
+        assert hist[0] == 0 and sum(a * h for a, h in enumerate(hist)) == gen_len
+        assert st["forwards"] <= gen_len and (N > 0 or st["forwards"] == gen_len)
+
+
+@pytest.mark.parametrize("N,refresh,block", [(3, 8, 8), (4, 8, 8), (3, 4, 8), (4, 32, 32), (2, 16, 8)])
+def test_dual_cache_closed_form_with_zero_attention(tiny, N, refresh, block):
+    """Zero attention output projections: no position sees any other, cached or not, every draft
+    verifies in left-to-right order.  Between two refreshes (or up to the end of the block, whichever
+    comes first) e tokens cost 1 + ceil((e - 1) / (N + 1)) forwards; the paper's setting (refresh =
+    block = 8) gives n_blocks * (1 + ceil(7 / (N + 1)))."""
+    cfg, w0 = tiny
+    w = dict(w0)
+    w["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w0["layers"]]
+    prompt = synth.gen_prompt(cfg, 3, 20)
+    gen_len = 64
+    out, st = decode.ssd_dual(w, cfg, prompt, gen_len, block, N, refresh)
+    assert out == decode.stepwise(w, cfg, prompt, gen_len, block)[0]       # the cache plays no part here
+    # the bookkeeping alone, every draft accepted: a block's first forward has no drafts and decodes
+    # one token; a chain decodes min(N + 1, tokens left in the block, tokens left until the refresh)
+    want, since = 0, refresh
+    for _ in range(gen_len // block):
+        left, first = block, True
+        while left:
+            if since >= refresh:
+                since, e = 0, 1
+            else:
+                e = 1 if first else min(N + 1, left, refresh - since)
+            want, since, left, first = want + 1, since + e, left - e, False
+    assert st["forwards"] == want, (st, want)
+    if refresh == block:
+        assert want == (gen_len // block) * (1 + math.ceil((block - 1) / (N + 1)))

@@ -214,6 +214,35 @@ int ssd_set_boundary_fusion(ssd_ctx* ctx, int on);
  * previous value or an error. */
 int ssd_set_cross_block(ssd_ctx* ctx, int on);
 
+/* Cache of the paper's experiments (Section 4.1: the prefix and suffix cache, refreshed every fixed
+ * number of decoded tokens).  mode 0 (default) = the exact block-causal prefix cache: a block sees
+ * the prompt, the finished blocks and itself.  mode 1 = dual cache: a refresh is one forward over
+ * the WHOLE sequence (prompt, decoded tokens, every still masked position up to the generation
+ * length) with full bidirectional attention; it renews the keys and values of all positions and is
+ * itself the decoding step of that moment.  Between refreshes only the current block is computed,
+ * against the cached keys and values of all other positions, before and behind it.  ssd_generate
+ * refreshes at the start and whenever refresh_interval tokens have been decoded since the last
+ * refresh (0 = the block length); a chain never carries more drafts than fit before the next
+ * refresh, so SSD and stepwise decoding (draft_depth 0) refresh at the same states and generate the
+ * same tokens.  Needs max_rows >= the sum of prompt + generation lengths of the sequences decoded
+ * together.  In mode 1 ssd_generate uses the greedy chain inside the block (tree mode, boundary
+ * fusion and cross-block rounds do not apply); stats.kv_passes counts the refreshes, each of which
+ * is also counted in stats.forwards.  Returns the previous mode or an error. */
+int ssd_set_cache_mode(ssd_ctx* ctx, int mode, int refresh_interval);
+
+/* One cache refresh of the dual cache (Section 4.1) for sequence `seq`, as a call of its own:
+ * tokens[0..total_len) (host) is the whole sequence, mask id at every position not decoded yet;
+ * the current block is [pos0, pos0 + block_len) and must hold at least one mask.  Runs all
+ * total_len rows with full bidirectional attention, writes every position's keys and values to the
+ * cache, and treats the block's rows like ssd_draft does: per-row outputs, the stepwise choice and
+ * n_draft_next next drafts go to `out` (slot 0) and to the sequence's device state.  Afterwards the
+ * slot's prefix length is pos0 and positions [pos0 + block_len, total_len) count as cached suffix:
+ * ssd_draft / ssd_verify_tree on this block (pos0 unchanged) attend to both.  ssd_prefill_kv and
+ * ssd_reset drop the suffix again.  Asynchronous.  Errors: SSD_ERANGE (total_len > max_rows or
+ * max_seq_len, block outside the sequence, token id out of range), SSD_EINVAL (no mask in the block). */
+int ssd_refresh_kv(ssd_ctx* ctx, int seq, const int32_t* tokens, int total_len, int pos0, int block_len,
+                   int n_draft_next, const ssd_step_out* out);
+
 /* Shape of the verification tree of ssd_verify_tree / ssd_generate:
  * 0 = the greedy chain of n_draft + 1 nodes (Section 3.2.3), 1 = the mix-order
  * tree (Section 5.2, Table 3): the chain plus, for every chain node but the last

@@ -20,6 +20,7 @@ SSD_F32, SSD_BF16 = 0, 1
 
 EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd_cached_len", "ssd_prefill_kv",
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_graphs", "ssd_set_tree_mode", "ssd_set_cross_block",
+           "ssd_set_cache_mode", "ssd_refresh_kv",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
            "ssd_debug_stream_read"]
@@ -79,6 +80,9 @@ def load_library() -> C.CDLL:
     lib.ssd_set_graphs.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cross_block.argtypes = [C.c_void_p, C.c_int]
+    lib.ssd_set_cache_mode.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    lib.ssd_refresh_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                   C.POINTER(SsdStepOut)]
     for n in ("ssd_profile_begin", "ssd_profile_end"):
         getattr(lib, n).argtypes = [C.c_void_p]
     lib.ssd_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
@@ -218,6 +222,14 @@ class SSD:
 
     def set_cross_block(self, on):
         return self._chk(self.lib.ssd_set_cross_block(self.h, int(on)))
+
+    def set_cache_mode(self, mode, refresh_interval=0):
+        return self._chk(self.lib.ssd_set_cache_mode(self.h, int(mode), int(refresh_interval)))
+
+    def refresh_kv(self, seq, tokens, pos0, block_len, n_draft_next, out):
+        t = _i32(tokens)
+        self._chk(self.lib.ssd_refresh_kv(self.h, seq, t.ctypes.data, len(t), pos0, block_len, n_draft_next,
+                                          C.byref(out.c)))
 
     def set_graphs(self, on):
         return self._chk(self.lib.ssd_set_graphs(self.h, int(on)))

@@ -697,23 +697,33 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
         for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
     float m_run = -INFINITY, l_part = 0.f;
 
-    const int pre_tiles = (nd.S + 31) >> 5, n_tiles = pre_tiles + ((nd.blen + 31) >> 5);
-    // positions past the end of the prefix or of the node hold stale memory: masked (keys) or zeroed (values)
+    // Key tiles, in this order: the cached prefix [0, S); the cached suffix [S + blen, T) of a
+    // sequence whose positions behind the block are cached too (T = 0: none); the node's own rows.
+    // Cache tiles are whole 32-position tiles of the cache; a tile may hold the end of the prefix and
+    // the start of the suffix at once, tiles that lie inside the block are skipped, and every tile
+    // listed holds at least one valid key.
+    const int blk_end = nd.S + nd.blen;
+    const int pre_tiles = (nd.S + 31) >> 5;
+    const int suf_first = max(pre_tiles, blk_end >> 5);
+    const int suf_tiles = nd.T > blk_end ? max(((nd.T + 31) >> 5) - suf_first, 0) : 0;
+    const int cache_tiles = pre_tiles + suf_tiles, n_tiles = cache_tiles + ((nd.blen + 31) >> 5);
+    auto cache_tile = [&](int t) { return t < pre_tiles ? t : suf_first + (t - pre_tiles); };
+    // positions that are not keys of this node hold other or stale data: masked (keys) or zeroed (values)
     auto load_k = [&](bf16x8(&kf)[KST], int t) {
         const bf16_t* kp;
-        if (t >= pre_tiles)
-            kp = (FUSED ? ks_own : ko + (size_t)(t - pre_tiles) * 32 * DH) + lane * 8;
+        if (t >= cache_tiles)
+            kp = (FUSED ? ks_own : ko + (size_t)(t - cache_tiles) * 32 * DH) + lane * 8;
         else
-            kp = kc + (size_t)t * 32 * DH + lane * 8;
+            kp = kc + (size_t)cache_tile(t) * 32 * DH + lane * 8;
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks) kf[ks] = *(const bf16x8*)(kp + ks * 512);
     };
     auto load_v = [&](bf16x8(&vf)[DT][2], int t) {
         const bf16_t* vp;
-        if (t >= pre_tiles)
-            vp = (FUSED ? vs_own : vo + (size_t)(t - pre_tiles) * 32 * DH) + lane * 8;
+        if (t >= cache_tiles)
+            vp = (FUSED ? vs_own : vo + (size_t)(t - cache_tiles) * 32 * DH) + lane * 8;
         else
-            vp = vc + (size_t)t * 32 * DH + lane * 8;
+            vp = vc + (size_t)cache_tile(t) * 32 * DH + lane * 8;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -722,7 +732,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     bf16x8 kf[KST], kn[KST], vf[DT][2], vn[DT][2];
     // the first tile's loads go out before anything else (FUSED: unless it is the own tile, which is
     // not in LDS yet)
-    const bool first_later = FUSED && wave >= pre_tiles;
+    const bool first_later = FUSED && wave >= cache_tiles;
     if (wave < n_tiles && !first_later) {
         load_k(kf, wave);
         load_v(vf, wave);
@@ -797,9 +807,14 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
         load_v(vf, wave);
     }
     for (int t = wave; t < n_tiles; t += ATTN_WAVES) {
-        const bool own = t >= pre_tiles;
-        const int t0 = (own ? t - pre_tiles : t) * 32;              // first key of the tile, in its own index space
-        const int n_valid = (own ? nd.blen : nd.S) - t0;            // keys of this tile that exist (may exceed 32)
+        const bool own = t >= cache_tiles;
+        // first key of the tile: a row of the node (own) or a cache position
+        const int t0 = (own ? t - cache_tiles : cache_tile(t)) * 32;
+        // keys t0 + [0, lim_a) and t0 + [lo_b, lim_b) of this tile exist
+        const int lim_a = (own ? nd.blen : nd.S) - t0;
+        const int lo_b = own ? 32 : blk_end - t0, lim_b = own ? 0 : nd.T - t0;
+        auto valid = [&](int key) { return key < lim_a || (key >= lo_b && key < lim_b); };
+        const bool all_valid = lim_a >= 32 || (lo_b <= 0 && lim_b >= 32);
         // ---- this wave's next tile, in flight while this one is processed
         if (t + ATTN_WAVES < n_tiles) {
             load_k(kn, t + ATTN_WAVES);
@@ -819,7 +834,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int key = (i >> 2) * 8 + lh * 4 + (i & 3);
-            sacc[i] = key < n_valid ? sacc[i] * scale : -INFINITY;
+            sacc[i] = valid(key) ? sacc[i] * scale : -INFINITY;
             mx = fmaxf(mx, sacc[i]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
@@ -835,8 +850,8 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
             pf[i >> 3][i & 7] = (__bf16)p;
         }
         l_part = l_part * corr + psum;
-        if (n_valid < 32) {
-            // positions past the end hold stale memory: zero them so 0 * garbage cannot produce NaN
+        if (!all_valid) {
+            // positions that are not keys hold other data: zero them so 0 * garbage cannot produce NaN
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -844,7 +859,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const int key = (2 * st + (j >> 2)) * 8 + lh * 4 + (j & 3);
-                        if (key >= n_valid) vf[dt][st][j] = (__bf16)0.f;
+                        if (!valid(key)) vf[dt][st][j] = (__bf16)0.f;
                     }
         }
 #pragma unroll

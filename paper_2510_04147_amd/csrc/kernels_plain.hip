@@ -255,7 +255,7 @@ __global__ __launch_bounds__(256) void k_rope(const FwdHeader* __restrict__ fw, 
 }
 
 // a4 (plain): one wave per (row, query head).  Keys = the sequence's cached
-// prefix [0,S) followed by the node's own rows; online softmax in fp32 over
+// prefix [0,S), its cached suffix behind the block if it has one, then the node's own rows; online softmax in fp32 over
 // key tiles of 64 in position order.
 template <typename T>
 __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__ fw, const int* __restrict__ row_node,
@@ -276,16 +276,19 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
     const T* vc = vcache + cbase;
     const T* ko = kown + (size_t)kvh * vt_rows * dh;
     const T* vo = vown + (size_t)kvh * vt_rows * dh;
-    const int n_keys = nd.S + nd.blen;
+    // keys: the cached prefix [0, S), the cached suffix [S + blen, T) if the sequence has one, the node's own rows
+    const int n_suf = max(nd.T - (nd.S + nd.blen), 0), n_cache = nd.S + n_suf;
+    const int n_keys = n_cache + nd.blen;
+    auto cache_pos = [&](int j) { return j < nd.S ? j : j + nd.blen; };
     const float scale = 1.0f / sqrtf((float)dh);
     float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
     for (int t0 = 0; t0 < n_keys; t0 += 64) {
         const int j = t0 + lane;
         float s = -INFINITY;
         if (j < n_keys) {
-            const bool pre = j < nd.S;
+            const bool pre = j < n_cache;
             const T* kp = pre ? kc : ko;
-            const int p = pre ? j : nd.vrow0 + j - nd.S;
+            const int p = pre ? cache_pos(j) : nd.vrow0 + j - n_cache;
             float acc = 0.f;
             for (int i = 0; i < dh; ++i) acc += qs[i] * ld_f(kp + kfrag_off(p, i, dh));
             s = acc * scale;
@@ -300,9 +303,9 @@ __global__ __launch_bounds__(64) void k_attn_plain(const FwdHeader* __restrict__
         for (int jj = 0; jj < cnt; ++jj) {
             const float pj = __shfl(p, jj, 64);
             const int jk = t0 + jj;
-            const bool pre = jk < nd.S;
+            const bool pre = jk < n_cache;
             const T* vp = pre ? vc : vo;
-            const int pp = pre ? jk : nd.vrow0 + jk - nd.S;
+            const int pp = pre ? cache_pos(jk) : nd.vrow0 + jk - n_cache;
             o0 += pj * ld_f(vp + vfrag_off(pp, lane, dh));
             if (dh > 64) o1 += pj * ld_f(vp + vfrag_off(pp, lane + 64, dh));
         }

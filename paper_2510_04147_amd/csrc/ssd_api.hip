@@ -188,6 +188,9 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->fuse_boundary = 1;
     c->tree_mode = 0;
     c->cross_block = 0;
+    c->cache_mode = 0;
+    c->refresh_interval = 0;
+    memset(c->total_len, 0, sizeof c->total_len);
     c->use_graphs = 0;
     memset(c->cached_len, 0, sizeof c->cached_len);
     c->profiling = false; c->ev_used = 0;
@@ -252,6 +255,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_reset(ssd_ctx* c, int 
     if (!c) return SSD_EINVAL;
     if (seq < 0 || seq >= c->dm.max_seqs) { set_err(c, "seq %d out of range", seq); return SSD_ERANGE; }
     c->cached_len[seq] = 0;
+    c->total_len[seq] = 0;
     return SSD_OK;
 }
 
@@ -279,6 +283,14 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_cross_block(ssd_ct
     if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
     const int old = c->cross_block;
     c->cross_block = on;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_cache_mode(ssd_ctx* c, int mode, int refresh_interval) {
+    if (!c || (mode != 0 && mode != 1) || refresh_interval < 0) return SSD_EINVAL;
+    const int old = c->cache_mode;
+    c->cache_mode = mode;
+    c->refresh_interval = refresh_interval;
     return old;
 }
 
@@ -518,7 +530,8 @@ static int mix_nodes(const ssd_ctx* c, int n_draft) { return c->tree_mode == 1 &
 // Appends a group to a header: n_chain chain nodes (node j holds drafts 1..j), then n_extra mix-order
 // nodes (node m holds drafts 1..m and m+2); returns the rows it takes.
 static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_chain, int n_extra, int n_draft_next,
-                     int fresh, int raw_off, int out_off, int allow_full = 0, bool leaf_writes_kv = false) {
+                     int fresh, int raw_off, int out_off, int allow_full = 0, bool leaf_writes_kv = false,
+                     int T = 0) {
     GroupDesc& g = hd.groups[hd.n_groups];
     const int n_nodes = n_chain + n_extra;
     g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
@@ -532,6 +545,7 @@ static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_ch
         nd.extra = j < n_chain ? -1 : j - n_chain + 1;
         nd.write_kv = mode != GM_DECODE || (leaf_writes_kv && j == n_chain - 1);
         nd.vrow0 = vrows;
+        nd.T = T;
         vrows += (blen + 63) & ~63;
     }
     hd.n_groups++;
@@ -557,7 +571,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_prefill_kv(ssd_ctx* c,
     memset(&hd, 0, sizeof hd);
     add_group(hd, seq, GM_RAW, n, pos0, 1, 0, 0, 0, 0, -1);
     int rc = run_forward(c, hd, tokens, n, nullptr, 0, nullptr);
-    if (rc == SSD_OK) c->cached_len[seq] = pos0 + n;
+    if (rc == SSD_OK) { c->cached_len[seq] = pos0 + n; c->total_len[seq] = 0; }   // prefix-only cache again
     return rc;
 }
 
@@ -619,7 +633,8 @@ static int step_common(ssd_ctx* c, const char* who, int n, const int* seqs, cons
             s.draft_tok[j] = t;
         }
         if (hd.M + (nd + 1 + mix_nodes(c, nd)) * bl > d.max_rows) { set_err(c, "%s: forward exceeds max_rows", who); return SSD_ERANGE; }
-        add_group(hd, seq, GM_DECODE, bl, p0, nd + 1, mix_nodes(c, nd), n_draft_next, 0, 0, -1);
+        add_group(hd, seq, GM_DECODE, bl, p0, nd + 1, mix_nodes(c, nd), n_draft_next, 0, 0, -1, 0, false,
+                  accept_only ? 0 : c->total_len[seq]);
     }
     return run_forward(c, hd, nullptr, 0, ups, n, out, k_conf, k_arg);
 }
@@ -639,6 +654,157 @@ extern "C" __attribute__((visibility("default"))) int ssd_verify_tree(ssd_ctx* c
                        n_draft, n_draft_next, out);
 }
 
+// ------------------------------------------------ dual cache (Section 4.1)
+// The three segments of a cache refresh for one sequence: the current block (a decode group whose one
+// node also writes its KV), then, as raw-token groups appended by refresh_tail, everything before and
+// everything behind it.  All three write their keys and values in each layer's rotary kernel, before
+// that layer's attention kernel, and read every other position from the cache (NodeDesc::T): together
+// one forward over the whole sequence with full bidirectional attention.
+static void refresh_head(FwdHeader& hd, int seq, int pos0, int bl, int T, int n_draft_next, int fresh) {
+    add_group(hd, seq, GM_DECODE, bl, pos0, 1, 0, n_draft_next, fresh, 0, -1, 0, true, T);
+}
+static void refresh_tail(FwdHeader& hd, int seq, const int32_t* tokens, int pos0, int bl, int T,
+                         std::vector<int32_t>& raw) {
+    if (pos0 > 0) {
+        add_group(hd, seq, GM_RAW, pos0, 0, 1, 0, 0, 0, (int)raw.size(), -1, 0, false, T);
+        raw.insert(raw.end(), tokens, tokens + pos0);
+    }
+    if (T > pos0 + bl) {
+        add_group(hd, seq, GM_RAW, T - pos0 - bl, pos0 + bl, 1, 0, 0, 0, (int)raw.size(), -1, 0, false, T);
+        raw.insert(raw.end(), tokens + pos0 + bl, tokens + T);
+    }
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_refresh_kv(ssd_ctx* c, int seq, const int32_t* tokens, int total_len, int pos0,
+                                                                     int block_len, int n_draft_next, const ssd_step_out* out) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!tokens || total_len < 1 || pos0 < 0 || block_len < 1) { set_err(c, "refresh: null tokens or bad lengths"); return SSD_EINVAL; }
+    if (seq < 0 || seq >= d.max_seqs) { set_err(c, "refresh: seq %d out of range", seq); return SSD_ERANGE; }
+    if (block_len > d.block || (long long)pos0 + block_len > total_len) { set_err(c, "refresh: block [%d, %d+%d) does not fit", pos0, pos0, block_len); return SSD_ERANGE; }
+    if (total_len > d.max_rows || total_len > d.max_seq_len) { set_err(c, "refresh: %d positions exceed max_rows / max_seq_len", total_len); return SSD_ERANGE; }
+    if (n_draft_next < 0 || n_draft_next > d.max_draft) { set_err(c, "refresh: n_draft_next out of range"); return SSD_ERANGE; }
+    for (int i = 0; i < total_len; ++i)
+        if (tokens[i] < 0 || tokens[i] >= d.V) { set_err(c, "refresh: token id %d out of range", tokens[i]); return SSD_ERANGE; }
+    Upload up;
+    memset(&up, 0, sizeof up);
+    up.seq = seq;
+    for (int p = 0; p < block_len; ++p) {
+        up.st.tok[p] = tokens[pos0 + p];
+        if (tokens[pos0 + p] == d.mask_id) up.st.masked |= 1ull << p;
+    }
+    if (!up.st.masked) { set_err(c, "refresh: no masked position in the block"); return SSD_EINVAL; }
+    FwdHeader hd;
+    memset(&hd, 0, sizeof hd);
+    std::vector<int32_t> raw;
+    refresh_head(hd, seq, pos0, block_len, total_len, n_draft_next, 0);
+    refresh_tail(hd, seq, tokens, pos0, block_len, total_len, raw);
+    int rc = run_forward(c, hd, raw.data(), (int)raw.size(), &up, 1, out);
+    if (rc == SSD_OK) { c->cached_len[seq] = pos0; c->total_len[seq] = total_len; }
+    return rc;
+}
+
+// ssd_generate with the dual cache: a forward over the whole sequence renews the cache at the start
+// and whenever refresh_interval tokens have been decoded since (0: the block length), and is itself the
+// decoding step of that moment; a chain carries no more drafts than fit before the next refresh, so
+// stepwise decoding and SSD refresh at the same states.  The host mirrors the sequences (the accepted
+// (position, token) pairs come back with every round) because a refresh feeds all of them in again.
+static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const int* prompt_len, int gen_len, int block,
+                         int draft_depth, int32_t* out_tokens, ssd_stats* stats) {
+    const Dims& d = c->dm;
+    const int R = c->refresh_interval > 0 ? c->refresh_interval : block;
+    long long rows_all = 0;
+    for (int i = 0; i < n; ++i) rows_all += prompt_len[i] + gen_len;
+    if (rows_all > d.max_rows) {
+        set_err(c, "generate: the dual cache refreshes whole sequences: %lld rows exceed max_rows %d", rows_all, d.max_rows);
+        return SSD_ERANGE;
+    }
+    const auto t_begin = std::chrono::steady_clock::now();
+    ssd_stats sta;
+    memset(&sta, 0, sizeof sta);
+    hipEvent_t ev0, ev1;
+    HIPCHK(c, hipEventCreate(&ev0));
+    HIPCHK(c, hipEventCreate(&ev1));
+    auto done = [&](int rc) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return rc; };
+    const int n_blocks = (gen_len + block - 1) / block;
+    std::vector<std::vector<int32_t>> x(n);
+    int blk[SSD_MAX_SEQS], n_masked[SSD_MAX_SEQS], n_dr[SSD_MAX_SEQS], since[SSD_MAX_SEQS];
+    bool start[SSD_MAX_SEQS], live_seq[SSD_MAX_SEQS], refresh_now[SSD_MAX_SEQS];
+    for (int i = 0; i < n; ++i) {
+        x[i].assign(prompts[i], prompts[i] + prompt_len[i]);
+        x[i].resize((size_t)prompt_len[i] + gen_len, d.mask_id);
+        blk[i] = 0; n_masked[i] = 0; n_dr[i] = 0; since[i] = R; start[i] = true; live_seq[i] = true;
+        c->total_len[i] = 0;
+    }
+    int live = n, rc;
+    std::vector<int32_t> raw;
+    while (live > 0) {
+        FwdHeader hd;
+        memset(&hd, 0, sizeof hd);
+        raw.clear();
+        for (int i = 0; i < n; ++i) {                       // decode groups first: their rows get logits
+            if (!live_seq[i]) continue;
+            const int S = prompt_len[i] + blk[i] * block, bl = std::min(block, gen_len - blk[i] * block);
+            const int T = prompt_len[i] + gen_len;
+            if (start[i]) { n_masked[i] = bl; n_dr[i] = 0; }
+            refresh_now[i] = since[i] >= R;
+            c->cached_len[i] = S;
+            if (refresh_now[i]) {
+                refresh_head(hd, i, S, bl, T, draft_depth, start[i]);
+            } else {
+                const int ndr = std::max(0, std::min(std::min(n_dr[i], n_masked[i] - 1), R - since[i] - 1));
+                add_group(hd, i, GM_DECODE, bl, S, ndr + 1, 0, draft_depth, start[i], 0, -1, 0, false, T);
+            }
+        }
+        for (int i = 0; i < n; ++i) {
+            if (!live_seq[i] || !refresh_now[i]) continue;
+            const int S = prompt_len[i] + blk[i] * block, bl = std::min(block, gen_len - blk[i] * block);
+            refresh_tail(hd, i, x[i].data(), S, bl, prompt_len[i] + gen_len, raw);
+            c->total_len[i] = prompt_len[i] + gen_len;
+        }
+        if (hd.M > d.max_rows) { set_err(c, "generate: forward exceeds max_rows"); return done(SSD_ERANGE); }
+        (void)hipEventRecord(ev0, c->stream);
+        if ((rc = run_forward(c, hd, raw.data(), (int)raw.size(), nullptr, 0, nullptr)) != SSD_OK) return done(rc);
+        HIPCHK(c, hipMemcpyAsync(c->host_result, c->b.result, sizeof(StepResult) * d.max_seqs, hipMemcpyDeviceToHost, c->stream));
+        (void)hipEventRecord(ev1, c->stream);
+        if (hipEventSynchronize(ev1) != hipSuccess) { set_err(c, "generate: sync failed: %s", hipGetErrorString(hipGetLastError())); return done(SSD_EHIP); }
+        float ms = 0; (void)hipEventElapsedTime(&ms, ev0, ev1);
+        sta.decode_ms += ms;
+        sta.forwards++;
+        for (int gi = 0; gi < hd.n_groups; ++gi) {
+            const GroupDesc& g = hd.groups[gi];
+            if (g.mode != GM_DECODE) continue;
+            const int i = g.seq;
+            const StepResult& r = c->host_result[i];
+            if (r.n_accept < 1 || r.n_accept > g.n_chain || r.n_accept > n_masked[i]) {
+                set_err(c, "generate: acceptance kernel returned %d for a chain of %d nodes", r.n_accept, g.n_chain);
+                return done(SSD_EHIP);
+            }
+            for (int k = 0; k < r.n_accept; ++k) {
+                if (r.acc_pos[k] < 0 || r.acc_pos[k] >= g.blen) { set_err(c, "generate: accepted position out of range"); return done(SSD_EHIP); }
+                x[i][(size_t)g.S + r.acc_pos[k]] = r.acc_tok[k];
+            }
+            sta.accept_hist[r.n_accept]++;
+            sta.tokens += r.n_accept;
+            if (refresh_now[i]) { since[i] = 0; sta.kv_passes++; }
+            since[i] += r.n_accept;
+            n_masked[i] -= r.n_accept;
+            n_dr[i] = r.n_next;
+            start[i] = false;
+            if (n_masked[i] == 0) {
+                blk[i]++;
+                start[i] = true;
+                if (blk[i] == n_blocks) { live_seq[i] = false; live--; }
+            }
+        }
+    }
+    for (int i = 0; i < n; ++i)
+        memcpy(out_tokens + (size_t)i * gen_len, x[i].data() + prompt_len[i], (size_t)gen_len * 4);
+    sta.total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
+    if (stats) *stats = sta;
+    return done(SSD_OK);
+}
+
 // ------------------------------------------------------------- Algorithm 1
 extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, int n, const int32_t* const* prompts, const int* prompt_len, int gen_len,
                             int block, int draft_depth, int32_t* out_tokens, ssd_stats* stats) {
@@ -655,6 +821,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
             return SSD_ERANGE;
         }
     }
+    if (c->cache_mode == 1) return generate_dual(c, n, prompts, prompt_len, gen_len, block, draft_depth, out_tokens, stats);
     const auto t_begin = std::chrono::steady_clock::now();
     ssd_stats sta;
     memset(&sta, 0, sizeof sta);

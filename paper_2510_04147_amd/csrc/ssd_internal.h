@@ -11,6 +11,8 @@
 #define SSD_MAX_SEQS 16
 // per sequence: the largest tree (2 * draft length nodes with mix order) plus a KV-append node
 #define SSD_MAX_NODES (SSD_MAX_SEQS * (2 * SSD_MAX_DRAFT + 1))
+// per sequence: a block's chain, the next block behind its leaf or a KV append, a cache refresh's three segments
+#define SSD_MAX_GROUPS (3 * SSD_MAX_SEQS)
 #define SSD_MAX_SPLIT 8
 
 // ---- forward descriptor (host-built, copied to the device before each forward)
@@ -42,12 +44,13 @@ struct NodeDesc {
     int extra;      // mix-order node: index of the one further draft written in (j + 1), else -1
     int write_kv;
     int vrow0;      // 64-aligned start of the node's rows in the own-key / own-value buffers
+    int T;          // dual cache (Section 4.1): positions [S + blen, T) are cached too and visible; 0 = prefix only
 };
 
 struct FwdHeader {
     int n_groups, n_nodes, M, M_logits;
     ssd_step_out out;            // where the acceptance kernel writes a step call's outputs (null pointers: nowhere)
-    GroupDesc groups[SSD_MAX_SEQS];
+    GroupDesc groups[SSD_MAX_GROUPS];
     NodeDesc nodes[SSD_MAX_NODES];
 };
 
@@ -89,7 +92,10 @@ struct Dims {
     // positions allocated per cache slot: whole 64-position tiles, so tile loads stay in bounds
     int seq_stride() const { return (max_seq_len + 63) & ~63; }
     // most nodes one forward of this context can hold
-    int max_nodes() const { return max_seqs * ((2 * max_draft > max_draft + 1 ? 2 * max_draft : max_draft + 1) + 1); }
+    int max_nodes() const {
+        const int tree = 2 * max_draft > max_draft + 1 ? 2 * max_draft : max_draft + 1;
+        return max_seqs * (tree + 1 > 3 ? tree + 1 : 3);           // a cache refresh takes three nodes
+    }
     // rows of the own-key / own-value buffers: every node starts on a 64-row boundary
     int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * max_nodes(); }
 };
@@ -185,6 +191,11 @@ struct ssd_ctx {
         hipGraphExec_t exec;
     };
     std::vector<FwdGraph> graphs;
+    // Cache of the paper's experiments (Section 4.1), 0 = exact block-causal prefix cache: 1 = dual
+    // cache, keys and values of ALL positions renewed by a full forward every refresh_interval
+    // decoded tokens (0 = once per block).  total_len[seq] > 0: positions up to there are cached.
+    int cache_mode, refresh_interval;
+    int total_len[SSD_MAX_SEQS];
     int cached_len[SSD_MAX_SEQS];
     // host staging ring for descriptors / small uploads
     static const int kSlots = 4;

@@ -159,3 +159,41 @@ def teacher_forced(eng, cfg, w, prompt, gen_len, block, N, dtype, max_blocks=Non
         totals["forwards"] += 1
     totals["rms_dlogit"] = math.sqrt(totals["sq_dlogit"] / max(totals["rows"], 1))
     return ref, st, totals
+
+
+def teacher_forced_dual(eng, cfg, w, prompt, gen_len, block, N, refresh, dtype, seq=0, verbose=True, max_forwards=None,
+                        **tol):
+    """As teacher_forced, for the dual cache with periodic refresh (Section 4.1): a recorded refresh is
+    replayed through ssd_refresh_kv with the oracle's whole sequence, every other forward through
+    ssd_verify_tree against the prefix and suffix that refresh cached."""
+    trace = []
+    ref, st = decode.ssd_dual(w, cfg, prompt, gen_len, block, N, refresh, dtype=dtype, trace=trace,
+                              max_forwards=max_forwards)
+    eng.reset(seq)
+    out = eng.new_out(1)
+    totals = dict(rows=0, tok_exempt=0, decision_exempt=0, max_dlogit=0.0, forwards=0, refreshes=0, sq_dlogit=0.0)
+    last_x = None
+    for i, rec in enumerate(trace):
+        bl = len(rec["tok"])
+        if verbose:
+            print(f"forward {i}: S={rec['S']} drafts={len(rec['drafts'])} refresh={rec['refresh']}", flush=True)
+        if rec["refresh"]:
+            eng.refresh_kv(seq, rec["x"], rec["S"], bl, N, out)
+            last_x = rec["x"]
+            totals["refreshes"] += 1
+        else:
+            if eng.cached_len(seq) != rec["S"]:
+                # a block that starts between two refreshes: the cache keeps the last refresh's keys and
+                # values, which the library can only be given by repeating that refresh for the new block
+                eng.refresh_kv(seq, last_x, rec["S"], bl, N, out)
+            eng.verify_tree([seq], [rec["tok"]], [bits(rec["masked"])], [rec["S"]], [rec["drafts"]], N, out,
+                            block_len=[bl])
+        g = {k: v[0] for k, v in out.host().items()}
+        s = check_forward(rec, g, N, **tol)
+        for k in ("rows", "tok_exempt", "decision_exempt"):
+            totals[k] += s[k]
+        totals["max_dlogit"] = max(totals["max_dlogit"], s["max_dlogit"])
+        totals["sq_dlogit"] += s["sq_dlogit"]
+        totals["forwards"] += 1
+    totals["rms_dlogit"] = math.sqrt(totals["sq_dlogit"] / max(totals["rows"], 1))
+    return ref, st, totals

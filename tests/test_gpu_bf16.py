@@ -151,6 +151,34 @@ def test_gpu_ssd_equals_gpu_stepwise_bf16(shallow8b):
     assert np.array_equal(both[0], base[0]) and np.array_equal(both[1], solo[0])
 
 
+def test_dual_cache_with_periodic_refresh_bf16(shallow8b):
+    """Section 4.1's cache on the MFMA path: refresh forwards (the whole sequence in three segments that
+    write and read the cache in the same layer) and block forwards against prefix + suffix, teacher
+    forced against the oracle; free running, SSD equals stepwise decoding bit for bit."""
+    cfg, w, wg, eng, prompt, sigma = shallow8b
+    tol = parity_util.bf16_tolerances(sigma)
+    try:
+        for (blk, N, R, mf) in ((32, 4, 4, 8), (8, 3, 8, 10)):
+            ref, st, tot = parity_util.teacher_forced_dual(eng, cfg, w, prompt, 48, blk, N, R, torch.float32,
+                                                           max_forwards=mf, **tol)
+            print(f"dual cache, block {blk}:", tot)
+            assert tot["refreshes"] >= 2 and tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
+            assert tot["tok_exempt"] <= 0.10 * tot["rows"]
+        for (blk, R) in ((8, 8), (32, 8), (24, 0)):
+            eng.set_cache_mode(1, R)
+            base, s0 = eng.generate([prompt], 56, blk, 0)
+            assert s0["forwards"] == 56
+            out, st = eng.generate([prompt], 56, blk, 4)
+            assert np.array_equal(out, base), (blk, R)
+            assert st["kv_passes"] == s0["kv_passes"] and st["forwards"] <= s0["forwards"]
+            print(f"dual cache block {blk} refresh {R}: forwards {st['forwards']} (stepwise 56), refreshes {st['kv_passes']}")
+    finally:
+        eng.set_cache_mode(0)
+    plain, _ = eng.generate([prompt], 56, 8, 4)
+    again, _ = eng.generate([prompt], 56, 8, 0)
+    assert np.array_equal(plain, again)
+
+
 def test_graph_replay_of_the_mfma_forward(shallow8b):
     """HIP-graph replay (off by default) of the bf16 forward with its MFMA kernels: a context on a side
     stream, graphs on, must generate the same tokens and run the same number of forwards."""

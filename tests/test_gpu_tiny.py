@@ -290,6 +290,67 @@ def test_round_across_the_block_boundary(setup):
         eng.close()
 
 
+def test_dual_cache_with_periodic_refresh(setup):
+    """Section 4.1 (ssd_set_cache_mode): the prefix + suffix cache, renewed by a forward over the whole
+    sequence every `refresh` decoded tokens.  Every forward, refreshes included, is compared with the
+    oracle teacher forced; free running, SSD equals stepwise decoding on the GPU bit for bit, and tokens,
+    forwards, refreshes and the acceptance histogram equal the oracle's ssd_dual."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=32, max_draft=8, max_rows=2 * 9 * 32)
+    tol = dict(maxlogit_tol=MAXLOGIT_TOL, margin_tol=MARGIN_TOL, conf_tol=CONF_TOL, conf_rtol=CONF_RTOL)
+    try:
+        # prompt 37 + block 8: blocks start in the middle of a 32-position cache tile, the suffix too
+        for (P, gen, blk, N, R) in ((37, 40, 8, 4, 8), (64, 64, 32, 4, 8), (20, 27, 8, 3, 5)):
+            prompt = synth.gen_prompt(cfg, 100 + P, P)
+            ref, so, tot = parity_util.teacher_forced_dual(eng, cfg, w, prompt, gen, blk, N, R, torch.float64,
+                                                           verbose=False, **tol)
+            print(f"dual P={P} block={blk} N={N} R={R}:", tot)
+            assert tot["forwards"] == so["forwards"] and tot["refreshes"] >= so["refreshes"]
+            assert tot["tok_exempt"] <= 0.02 * tot["rows"] and tot["decision_exempt"] <= 2
+        for (P, gen, blk, R) in ((37, 40, 8, 8), (48, 64, 32, 8), (30, 40, 8, 11), (30, 40, 8, 0), (30, 24, 8, 1000)):
+            prompt = synth.gen_prompt(cfg, 200 + P, P)
+            assert eng.set_cache_mode(1, R) in (0, 1)
+            base, s0 = eng.generate([prompt], gen, blk, 0)
+            Re = R if R > 0 else blk
+            assert s0["forwards"] == gen and s0["kv_passes"] == math.ceil(gen / min(Re, gen))
+            want, _ = decode.stepwise_dual(w, cfg, prompt, gen, blk, Re)
+            same = list(base[0]) == want
+            for N in (1, 3, 8):
+                out, st = eng.generate([prompt], gen, blk, N)
+                assert np.array_equal(out, base), (P, R, N)
+                assert st["tokens"] == gen and st["kv_passes"] == s0["kv_passes"]
+                if same:                                   # no near-tie anywhere: the rounds must agree too
+                    ro, so = decode.ssd_dual(w, cfg, prompt, gen, blk, N, Re)
+                    assert st["forwards"] == so["forwards"], (P, R, N, st, so)
+                    assert st["accept_hist"][:N + 2] == so["accept_hist"][:N + 2]
+            eng.set_cache_mode(0)
+            plain, _ = eng.generate([prompt], gen, blk, 0)
+            assert not np.array_equal(plain, base)         # the suffix is really seen: other tokens than block-causal
+        # two sequences at once: each refreshes on its own schedule
+        p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)
+        eng.set_cache_mode(1, 8)
+        both, st = eng.generate([p0, p1], 40, 8, 3)
+        a, _ = eng.generate([p0], 40, 8, 0)
+        b, _ = eng.generate([p1], 40, 8, 0)
+        assert np.array_equal(both[0], a[0]) and np.array_equal(both[1], b[0]) and st["tokens"] == 80
+        # the exact cache is back afterwards, suffix forgotten
+        eng.set_cache_mode(0)
+        again, _ = eng.generate([p0], 40, 8, 3)
+        eng2, _ = eng.generate([p0], 40, 8, 0)
+        assert np.array_equal(again, eng2)
+        # errors: launched nothing
+        out = eng.new_out(1)
+        with pytest.raises(binding.SsdError):
+            eng.refresh_kv(0, [1] * 40, 8, 8, 2, out)                      # no masked position in the block
+        with pytest.raises(binding.SsdError):
+            eng.refresh_kv(0, [cfg["mask_id"]] * 40, 36, 8, 2, out)        # block beyond the sequence
+        with pytest.raises(binding.SsdError):
+            eng.refresh_kv(0, [cfg["mask_id"]] * 1000, 0, 8, 2, out)       # more rows than max_rows
+    finally:
+        eng.close()
+
+
 def test_repeated_forward_is_bit_identical_and_node_independent(setup):
     cfg, w, wg, eng = setup
     prompt = synth.gen_prompt(cfg, 5, 40)

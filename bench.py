@@ -83,7 +83,7 @@ def main():
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         eng = binding.SSD(cfg, wg, max_seqs=nseq, max_seq_len=P + G, block=B, max_draft=N,
-                          max_rows=max(P, S, nseq * max(N + 2, 2 * N) * B))
+                          max_rows=max(P, S, nseq * max(N + 2, 2 * N) * B, nseq * (P + G)))
         # ---- verification forward at prefix S, fixed block state with N drafts, every sequence of the batch
         note(f"context created; prefill of {nseq} x {S} positions")
         for i in range(nseq):
@@ -200,6 +200,12 @@ def main():
             eng.set_cross_block(0)
             same = bool(np.array_equal(toks_ssd, toks_step) and np.array_equal(toks_mix, toks_step) and
                         np.array_equal(toks_x, toks_step))
+            # the cache of the paper's experiments (Section 4.1): prefix + suffix, renewed by a forward over the
+            # whole sequence every 8 decoded tokens; a different model function, so its own stepwise run
+            eng.set_cache_mode(1, 8)
+            toks_d, st_d = eng.generate(prompts, G, B, N)
+            toks_d0, st_d0 = eng.generate(prompts, G, B, 0)
+            eng.set_cache_mode(0)
             GT = G * nseq                                        # tokens generated over the whole batch
             gen = dict(
                 ssd_tokens_per_s=GT / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_step["total_ms"] / 1e3),
@@ -211,7 +217,12 @@ def main():
                 mix_order_tokens_per_s=GT / (st_mix["total_ms"] / 1e3), mix_order_forwards=st_mix["forwards"],
                 mix_order_accept_hist=st_mix["accept_hist"][:N + 2],
                 cross_block_tokens_per_s=GT / (st_x["total_ms"] / 1e3), cross_block_forwards=st_x["forwards"],
-                cross_block_kv_passes=st_x["kv_passes"])
+                cross_block_kv_passes=st_x["kv_passes"],
+                dual_cache=dict(refresh_interval=8, ssd_tokens_per_s=GT / (st_d["total_ms"] / 1e3),
+                                stepwise_tokens_per_s=GT / (st_d0["total_ms"] / 1e3), ssd_forwards=st_d["forwards"],
+                                stepwise_forwards=st_d0["forwards"], refreshes=st_d["kv_passes"],
+                                accept_hist=st_d["accept_hist"][:N + 2],
+                                ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0))))
 
     # ---- roofline arithmetic
     M = nseq * (N + 1) * B

@@ -35,6 +35,17 @@
                reaches past the next refresh, so SSD and stepwise decoding refresh
                at the same states and stay identical.
 
+  limit probe  acceptance_limit_probe: the procedure behind Table 2 (Section 5.1).
+               Stepwise decoding is cut into rounds of N+1 steps (a new round at every
+               block start); the logits of a round's first forward are what a draft
+               made at that moment would know.  A token decoded in the round counts
+               as matched for k if it is among the k highest-ranked tokens of those
+               logits at its position.  A round of n steps with m matched tokens would
+               have cost n - m + 1 forwards (one verification pass for the matched
+               ones, a step of its own for every other), which gives the reduction in
+               forwards an ideal verification tree could reach; m = n = N+1 in every
+               round is the table's upper bound N/(N+1).
+
 Readings where the paper is silent (all also applied by the HIP path):
   * confidence c = softmax probability of the arg-max token (Section 3.2.2);
   * the mask token can never be predicted (excluded from max / arg-max / sum);
@@ -463,6 +474,58 @@ def bruteforce_full(w, cfg, prompt, gen_len, block, dtype=torch.float64):
             p = stepwise_choice(c, masked)
             x[P + off + p], masked[p] = int(t[p]), False
     return x[P:]
+
+
+# --------------------------------------------------------------------------
+# acceptance-rate limit of self-drafting (Section 5.1, Table 2)
+# --------------------------------------------------------------------------
+def token_rank(logits_row, t, mask_id):
+    """Number of tokens ranked ahead of t in one row of logits: higher logit, or equal logit and lower
+    id; the mask token is never a candidate."""
+    ids = torch.arange(logits_row.shape[0])
+    ahead = ((logits_row > logits_row[t]) | ((logits_row == logits_row[t]) & (ids < t))) & (ids != mask_id)
+    return int(ahead.sum())
+
+
+def limit_from_ranks(rounds, k_max):
+    """rounds: per round the ranks (token_rank against the round's first logits) of the tokens its steps
+    decoded.  Returns per k = 1..k_max (matched tokens, forwards an ideal tree would need)."""
+    matched, forwards = [0] * k_max, [0] * k_max
+    for ranks in rounds:
+        for k in range(1, k_max + 1):
+            m = sum(1 for r in ranks if r < k)
+            matched[k - 1] += m
+            forwards[k - 1] += len(ranks) - m + 1        # m >= 1: a round's first token is its logits' arg-max
+    return matched, forwards
+
+
+def acceptance_limit_probe(w, cfg, prompt, gen_len, block, n_draft, k_max, dtype=torch.float64):
+    """Runs stepwise decoding (exact prefix cache) and records, per round of n_draft + 1 steps, how the
+    decoded tokens rank in the round's first logits.  Returns (tokens, dict(steps, rounds, ranks,
+    matched[k-1], forwards[k-1], reduction[k-1]))."""
+    P = len(prompt)
+    cache = _prefill(w, cfg, prompt, dtype)
+    out, rounds = [], []
+    for (off, Bj) in _blocks(gen_len, block):
+        S = P + off
+        tok, masked = [cfg["mask_id"]] * Bj, [True] * Bj
+        step_in_round, first_logits = 0, None
+        while any(masked):
+            logits, _ = forward_segment(w, cfg, tok, S, cache, dtype)
+            if step_in_round == 0:
+                first_logits = logits
+                rounds.append([])
+            t, _, c, _ = predict(logits, cfg["mask_id"])
+            p = stepwise_choice(c, masked)
+            rounds[-1].append(token_rank(first_logits[p], int(t[p]), cfg["mask_id"]))
+            tok[p], masked[p] = int(t[p]), False
+            step_in_round = (step_in_round + 1) % (n_draft + 1)
+        _, kv = forward_segment(w, cfg, tok, S, cache, dtype, need_logits=False)
+        cache.append(kv)
+        out += tok
+    matched, forwards = limit_from_ranks(rounds, k_max)
+    return out, dict(steps=gen_len, rounds=len(rounds), ranks=rounds, matched=matched, forwards=forwards,
+                     reduction=[1.0 - f / gen_len for f in forwards])
 
 
 def bruteforce(w, cfg, prompt, gen_len, block, dtype=torch.float64):

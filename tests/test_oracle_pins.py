@@ -527,3 +527,43 @@ def test_dual_cache_closed_form_with_zero_attention(tiny, N, refresh, block):
     assert st["forwards"] == want, (st, want)
     if refresh == block:
         assert want == (gen_len // block) * (1 + math.ceil((block - 1) / (N + 1)))
+
+
+# ------------------------------------------------- acceptance-rate limit probe (Section 5.1, Table 2)
+def test_token_rank_against_a_sort():
+    g = torch.Generator().manual_seed(3)
+    row = torch.randint(0, 6, (40,), generator=g).double()          # many ties
+    mask_id = 17
+    order = sorted((v for v in range(40) if v != mask_id), key=lambda v: (-float(row[v]), v))
+    for t in (0, 5, 16, 18, 39):
+        assert decode.token_rank(row, t, mask_id) == order.index(t)
+
+
+def test_limit_from_ranks_hand_made():
+    """Two rounds of four steps (N = 3) and a last round of two: ranks of the decoded tokens in the
+    round's first logits.  k = 1 matches ranks 0 only, k = 2 ranks 0 and 1, ..."""
+    rounds = [[0, 0, 1, 3], [0, 2, 0, 0], [0, 0]]
+    matched, forwards = decode.limit_from_ranks(rounds, 4)
+    assert matched == [2 + 3 + 2, 3 + 3 + 2, 3 + 4 + 2, 4 + 4 + 2]
+    assert forwards == [(4 - 2 + 1) + (4 - 3 + 1) + (2 - 2 + 1), 2 + 2 + 1, 2 + 1 + 1, 1 + 1 + 1]
+
+
+@pytest.mark.parametrize("N", [3, 4, 5])
+def test_acceptance_limit_probe_invariants_and_upper_bound(tiny, N):
+    """Table 2: more candidates per position can only match more; k = V - 1 (every token) matches all
+    steps and gives the table's upper bound, N/(N+1) when the rounds are full; with zero attention
+    the first logits already predict every later step, so k = 1 reaches the bound (the self-draft is
+    perfect there), which is what SSD itself achieves on that model."""
+    cfg, w0 = tiny
+    prompt = synth.gen_prompt(cfg, 9, 24)
+    gen_len, block = 2 * 6 * (N + 1), 6 * (N + 1)                     # whole rounds only
+    ref, _ = decode.stepwise(w0, cfg, prompt, gen_len, block)
+    out, pr = decode.acceptance_limit_probe(w0, cfg, prompt, gen_len, block, N, cfg["vocab"] - 1)
+    assert out == ref and pr["steps"] == gen_len and pr["rounds"] == gen_len // (N + 1)
+    assert all(r[0] == 0 for r in pr["ranks"])                          # a round's first token is the arg-max of its logits
+    assert all(a <= b for a, b in zip(pr["matched"], pr["matched"][1:]))
+    assert pr["matched"][-1] == gen_len and abs(pr["reduction"][-1] - N / (N + 1)) < 1e-12
+    w = dict(w0)
+    w["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w0["layers"]]
+    _, pz = decode.acceptance_limit_probe(w, cfg, prompt, gen_len, block, N, 3)
+    assert pz["matched"] == [gen_len] * 3 and abs(pz["reduction"][0] - N / (N + 1)) < 1e-12

@@ -206,6 +206,8 @@ def main():
             toks_d, st_d = eng.generate(prompts, G, B, N)
             toks_d0, st_d0 = eng.generate(prompts, G, B, 0)
             eng.set_cache_mode(0)
+            # the acceptance-rate limit of self-drafting (Section 5.1, the procedure of Table 2), first sequence
+            _, lim = eng.acceptance_limit(prompts[0], G, B, N, 5)
             GT = G * nseq                                        # tokens generated over the whole batch
             gen = dict(
                 ssd_tokens_per_s=GT / (st_ssd["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_step["total_ms"] / 1e3),
@@ -222,7 +224,9 @@ def main():
                                 stepwise_tokens_per_s=GT / (st_d0["total_ms"] / 1e3), ssd_forwards=st_d["forwards"],
                                 stepwise_forwards=st_d0["forwards"], refreshes=st_d["kv_passes"],
                                 accept_hist=st_d["accept_hist"][:N + 2],
-                                ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0))))
+                                ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0))),
+                acceptance_limit=dict(draft_length=N, reduction_top_k=[round(x, 4) for x in lim["reduction"]],
+                                      upper_bound=N / (N + 1), rounds=lim["rounds"]))
 
     # ---- roofline arithmetic
     M = nseq * (N + 1) * B

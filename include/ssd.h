@@ -243,6 +243,20 @@ int ssd_set_cache_mode(ssd_ctx* ctx, int mode, int refresh_interval);
 int ssd_refresh_kv(ssd_ctx* ctx, int seq, const int32_t* tokens, int total_len, int pos0, int block_len,
                    int n_draft_next, const ssd_step_out* out);
 
+/* Acceptance-rate limit of self-drafting (Section 5.1, the procedure behind Table 2), an analysis
+ * call.  Decodes prompt (host, prompt_len tokens) stepwise in sequence slot 0 with the exact prefix
+ * cache: gen_len tokens in blocks of `block`.  The steps are cut into rounds of n_draft + 1 (a new
+ * round at every block start); the logits of a round's first forward are kept, and every token the
+ * round decodes is ranked in them at its position (tokens with a higher logit, or an equal logit and
+ * a lower id, are ahead; the mask token is no candidate).  For k = 1 .. k_max (host arrays of k_max
+ * entries): matched[k-1] = tokens with rank < k, i.e. found among the k best candidates a draft made
+ * at the round's start would hold; forwards[k-1] = sum over rounds of (steps - matched + 1), the
+ * forwards an ideal verification tree would need; 1 - forwards / gen_len is the table's reduction,
+ * n_draft / (n_draft + 1) its upper bound.  *rounds (optional) = number of rounds; out_tokens
+ * (optional, host, gen_len entries) = the decoded tokens.  Synchronous.  Errors as ssd_generate. */
+int ssd_acceptance_limit(ssd_ctx* ctx, const int32_t* prompt, int prompt_len, int gen_len, int block, int n_draft,
+                         int k_max, int32_t* out_tokens, int64_t* matched, int64_t* forwards, int64_t* rounds);
+
 /* Shape of the verification tree of ssd_verify_tree / ssd_generate:
  * 0 = the greedy chain of n_draft + 1 nodes (Section 3.2.3), 1 = the mix-order
  * tree (Section 5.2, Table 3): the chain plus, for every chain node but the last

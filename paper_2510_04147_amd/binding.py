@@ -20,7 +20,7 @@ SSD_F32, SSD_BF16 = 0, 1
 
 EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd_cached_len", "ssd_prefill_kv",
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_graphs", "ssd_set_tree_mode", "ssd_set_cross_block",
-           "ssd_set_cache_mode", "ssd_refresh_kv",
+           "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
            "ssd_debug_stream_read"]
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cross_block.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cache_mode.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    lib.ssd_acceptance_limit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ssd_refresh_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                    C.POINTER(SsdStepOut)]
     for n in ("ssd_profile_begin", "ssd_profile_end"):
@@ -230,6 +232,18 @@ class SSD:
         t = _i32(tokens)
         self._chk(self.lib.ssd_refresh_kv(self.h, seq, t.ctypes.data, len(t), pos0, block_len, n_draft_next,
                                           C.byref(out.c)))
+
+    def acceptance_limit(self, prompt, gen_len, block, n_draft, k_max):
+        p = _i32(prompt)
+        toks = np.zeros(gen_len, dtype=np.int32)
+        matched, forwards = np.zeros(k_max, dtype=np.int64), np.zeros(k_max, dtype=np.int64)
+        rounds = np.zeros(1, dtype=np.int64)
+        self._chk(self.lib.ssd_acceptance_limit(self.h, p.ctypes.data, len(p), gen_len, block, n_draft, k_max,
+                                                toks.ctypes.data, matched.ctypes.data, forwards.ctypes.data,
+                                                rounds.ctypes.data))
+        return toks, dict(steps=gen_len, rounds=int(rounds[0]), matched=[int(v) for v in matched],
+                          forwards=[int(v) for v in forwards],
+                          reduction=[1.0 - int(f) / gen_len for f in forwards])
 
     def set_graphs(self, on):
         return self._chk(self.lib.ssd_set_graphs(self.h, int(on)))

@@ -788,6 +788,27 @@ __global__ void k_sum_partials(const float* __restrict__ part, int n_part, size_
     out[i] = v;
 }
 
+__global__ __launch_bounds__(256) void k_token_rank(const float* __restrict__ logits, int V, int mask_id, RankPairs pairs,
+                                                    int* __restrict__ rank) {
+    const int i = blockIdx.x;
+    const float* row = logits + (size_t)pairs.pos[i] * V;
+    const int t = pairs.tok[i];
+    const float lt = row[t];
+    int ahead = 0;
+    for (int v = threadIdx.x; v < V; v += 256)
+        ahead += v != mask_id && (row[v] > lt || (row[v] == lt && v < t));
+    __shared__ int part[4];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ahead += __shfl_xor(ahead, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ahead;
+    __syncthreads();
+    if (threadIdx.x == 0) rank[i] = part[0] + part[1] + part[2] + part[3];
+}
+
+void launch_token_rank(const float* logits, int V, int mask_id, const RankPairs& pairs, int* rank, hipStream_t st) {
+    if (pairs.n > 0) k_token_rank<<<pairs.n, 256, 0, st>>>(logits, V, mask_id, pairs, rank);
+}
+
 __global__ void k_int_to_float(const int* __restrict__ src, float* __restrict__ dst, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = (float)src[i];

@@ -131,6 +131,8 @@ static size_t carve(const Dims& d, char* base, Buffers* b) {
     t.state = (SeqState*)take(sizeof(SeqState) * SSD_MAX_SEQS);
     t.result = (StepResult*)take(sizeof(StepResult) * SSD_MAX_SEQS);
     t.out_tok = (int*)take((size_t)d.max_seqs * d.max_seq_len * 4);
+    t.probe_logits = (float*)take((size_t)d.block * d.V * 4);
+    t.probe_rank = (int*)take((SSD_MAX_DRAFT + 1) * 4);
     t.lm_tiles = tiles;
     if (b) *b = t;
     return (off + 255) & ~(size_t)255;
@@ -972,6 +974,72 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
     sta.total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     if (stats) *stats = sta;
     return done(SSD_OK);
+}
+
+// ------------------------------------------- acceptance-rate limit (Section 5.1, Table 2)
+extern "C" __attribute__((visibility("default"))) int ssd_acceptance_limit(ssd_ctx* c, const int32_t* prompt, int prompt_len, int gen_len,
+                                                                           int block, int n_draft, int k_max, int32_t* out_tokens,
+                                                                           int64_t* matched, int64_t* forwards, int64_t* rounds) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!prompt || prompt_len < 1 || gen_len < 1 || !matched || !forwards || k_max < 1) { set_err(c, "acceptance_limit: bad argument"); return SSD_EINVAL; }
+    if (block < 1 || block > d.block) { set_err(c, "acceptance_limit: block %d out of range", block); return SSD_ERANGE; }
+    if (n_draft < 0 || n_draft > SSD_MAX_DRAFT) { set_err(c, "acceptance_limit: n_draft out of range"); return SSD_ERANGE; }
+    if (prompt_len > d.max_rows || (long long)prompt_len + gen_len > d.max_seq_len) { set_err(c, "acceptance_limit: prompt (+gen_len) exceeds max_rows / max_seq_len"); return SSD_ERANGE; }
+    for (int k = 0; k < k_max; ++k) matched[k] = forwards[k] = 0;
+    int64_t n_rounds = 0;
+    int rc;
+    c->cached_len[0] = 0;
+    if ((rc = ssd_prefill_kv(c, 0, prompt, prompt_len, 0)) != SSD_OK) return rc;
+    std::vector<int32_t> blk_tok(d.block);
+    RankPairs pairs;
+    int rank[SSD_MAX_DRAFT + 1];
+    // ranks of a finished round against its first logits -> matched tokens and forwards of an ideal tree
+    auto close_round = [&]() -> int {
+        if (pairs.n == 0) return SSD_OK;
+        launch_token_rank(c->b.probe_logits, d.V, d.mask_id, pairs, c->b.probe_rank, c->stream);
+        HIPCHK(c, hipMemcpyAsync(rank, c->b.probe_rank, (size_t)pairs.n * 4, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        for (int k = 1; k <= k_max; ++k) {
+            int m = 0;
+            for (int i = 0; i < pairs.n; ++i) m += rank[i] < k;
+            matched[k - 1] += m;
+            forwards[k - 1] += pairs.n - m + (m > 0 ? 1 : 0);
+        }
+        n_rounds++;
+        pairs.n = 0;
+        return SSD_OK;
+    };
+    const int n_blocks = (gen_len + block - 1) / block;
+    for (int b = 0; b < n_blocks; ++b) {
+        const int S = prompt_len + b * block, bl = std::min(block, gen_len - b * block);
+        pairs.n = 0;
+        for (int step = 0; step < bl; ++step) {
+            FwdHeader hd;
+            memset(&hd, 0, sizeof hd);
+            add_group(hd, 0, GM_DECODE, bl, S, 1, 0, 0, step == 0, 0, -1);
+            if ((rc = run_forward(c, hd, nullptr, 0, nullptr, 0, nullptr)) != SSD_OK) return rc;
+            if (pairs.n == 0)   // a round's first forward: keep its logits (the normed rows are still in place)
+                launch_gemm_plain(c, EPI_F32, c->b.xn, c->lm_head.raw, c->b.probe_logits, bl, d.V, d.d, c->stream);
+            HIPCHK(c, hipMemcpyAsync(c->host_result, c->b.result, sizeof(StepResult), hipMemcpyDeviceToHost, c->stream));
+            HIPCHK(c, hipStreamSynchronize(c->stream));
+            const StepResult& r = c->host_result[0];
+            if (r.n_accept != 1 || r.acc_pos[0] < 0 || r.acc_pos[0] >= bl || r.acc_tok[0] < 0 || r.acc_tok[0] >= d.V) {
+                set_err(c, "acceptance_limit: a stepwise forward accepted %d tokens", r.n_accept);
+                return SSD_EHIP;
+            }
+            blk_tok[r.acc_pos[0]] = r.acc_tok[0];
+            pairs.pos[pairs.n] = r.acc_pos[0];
+            pairs.tok[pairs.n] = r.acc_tok[0];
+            pairs.n++;
+            if (pairs.n == n_draft + 1 && (rc = close_round()) != SSD_OK) return rc;
+        }
+        if ((rc = close_round()) != SSD_OK) return rc;          // a block's last round may be short
+        if (out_tokens) memcpy(out_tokens + (size_t)b * block, blk_tok.data(), (size_t)bl * 4);
+        if (b + 1 < n_blocks && (rc = ssd_prefill_kv(c, 0, blk_tok.data(), bl, S)) != SSD_OK) return rc;
+    }
+    if (rounds) *rounds = n_rounds;
+    return SSD_OK;
 }
 
 // ---------------------------------------------------------- kernel-level entry

@@ -152,6 +152,8 @@ struct Buffers {
     SeqState* state;     // [max_seqs]
     StepResult* result;  // [max_seqs]
     int* out_tok;        // [max_seqs, max_seq_len] device token output of ssd_generate
+    float* probe_logits; // [block, V] logits of a round's first forward (ssd_acceptance_limit)
+    int* probe_rank;     // [SSD_MAX_DRAFT + 1]
     int lm_tiles;        // vocab tiles of the LM-head reduction
 };
 
@@ -230,6 +232,10 @@ int lm_tiles_plain(int V);
 // out[M,N] = sum over the first n_part split-K partial buffers, in split order
 void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out, hipStream_t st);
 void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st);
+// rank[i] = number of tokens ahead of tok[i] in row pos[i] of logits [*, V]: higher logit, or equal and
+// lower id; the mask token never counts
+struct RankPairs { int n; int pos[SSD_MAX_DRAFT + 1]; int tok[SSD_MAX_DRAFT + 1]; };
+void launch_token_rank(const float* logits, int V, int mask_id, const RankPairs& pairs, int* rank, hipStream_t st);
 
 enum GemmEpi : int { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
 // out[M,N] = X[M,K] * W[N,K]^T with the plain FMA kernel.

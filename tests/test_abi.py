@@ -73,3 +73,4 @@ def test_config_validation_needs_no_gpu(lib):
         assert getattr(lib, name)(None, 1) == -1, name
     assert lib.ssd_set_cache_mode(None, 1, 8) == -1
     assert lib.ssd_refresh_kv(None, 0, None, 0, 0, 0, 0, None) == -1
+    assert lib.ssd_acceptance_limit(None, None, 0, 0, 0, 0, 0, None, None, None, None) == -1

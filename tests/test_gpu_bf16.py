@@ -8,6 +8,8 @@ vocab 126464), two layers deep so the CPU oracle finishes in seconds:
   * GPU SSD == GPU stepwise bit for bit, one- and multi-sequence, and a node's rows bit-identical
     whether computed alone or inside a 5-node forward.
 """
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -177,6 +179,23 @@ def test_dual_cache_with_periodic_refresh_bf16(shallow8b):
     plain, _ = eng.generate([prompt], 56, 8, 4)
     again, _ = eng.generate([prompt], 56, 8, 0)
     assert np.array_equal(plain, again)
+
+
+def test_acceptance_limit_probe_bf16(shallow8b):
+    """Section 5.1 / Table 2 on the 8B layer shape: the probe decodes the tokens stepwise decoding does,
+    more candidates never match fewer tokens, and forwards and matches add up per round."""
+    cfg, w, wg, eng, prompt, _ = shallow8b
+    base, _ = eng.generate([prompt], 48, 8, 0)
+    for N in (3, 5):
+        toks, pr = eng.acceptance_limit(prompt, 48, 8, N, 5)
+        assert np.array_equal(toks, base[0])
+        assert pr["rounds"] == 6 * math.ceil(8 / (N + 1))
+        assert all(a <= b for a, b in zip(pr["matched"], pr["matched"][1:])) and pr["matched"][-1] <= 48
+        assert all(f == 48 - m + pr["rounds"] for f, m in zip(pr["forwards"], pr["matched"]))
+        # the logits kept for ranking come from the plain GEMM, the decoded arg-max from the MFMA reduction:
+        # they may disagree on a near-tie, so a round's first token is rank 0 in all but a few rounds
+        assert pr["matched"][0] >= pr["rounds"] - 2
+        print(f"N={N}: reduction per k {[round(x, 3) for x in pr['reduction']]}")
 
 
 def test_graph_replay_of_the_mfma_forward(shallow8b):

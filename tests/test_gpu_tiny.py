@@ -351,6 +351,39 @@ def test_dual_cache_with_periodic_refresh(setup):
         eng.close()
 
 
+def test_acceptance_limit_probe(setup):
+    """Section 5.1 / Table 2 (ssd_acceptance_limit): rounds of N+1 stepwise steps, every decoded token
+    ranked in the round's first logits.  Tokens equal stepwise decoding; where they also equal the
+    oracle's (no near-tie on the way) the matched counts and ideal forwards per k equal the oracle's
+    probe; zero attention reaches the table's upper bound at k = 1."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, eng = setup
+    for (seed, P, gen, blk) in ((9, 24, 48, 24), (1001, 64, 64, 32), (8, 40, 40, 8)):
+        prompt = synth.gen_prompt(cfg, seed, P)
+        base, _ = eng.generate([prompt], gen, blk, 0)
+        for N in (3, 4, 5):
+            toks, pr = eng.acceptance_limit(prompt, gen, blk, N, 5)
+            assert np.array_equal(toks, base[0]), (seed, N)
+            ro, po = decode.acceptance_limit_probe(w, cfg, prompt, gen, blk, N, 5)
+            assert pr["rounds"] == po["rounds"]
+            assert all(a <= b for a, b in zip(pr["matched"], pr["matched"][1:]))
+            assert pr["matched"][0] >= pr["rounds"]                  # a round's first token always matches
+            if list(toks) == ro:
+                assert pr["matched"] == po["matched"] and pr["forwards"] == po["forwards"], (seed, N, pr, po)
+            print(f"seed {seed} block {blk} N={N}: reduction per k {[round(x, 3) for x in pr['reduction']]} bound {N / (N + 1):.3f}")
+    w0 = dict(w)
+    w0["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w["layers"]]
+    e0 = binding.SSD(cfg, synth.weights_to(w0, "cuda"), max_seqs=1, max_seq_len=256, block=32, max_draft=8,
+                     max_rows=9 * 32)
+    try:
+        toks, pr = e0.acceptance_limit(synth.gen_prompt(cfg, 3, 20), 60, 30, 4, 3)
+        assert pr["matched"] == [60] * 3 and abs(pr["reduction"][0] - 4 / 5) < 1e-12
+        with pytest.raises(binding.SsdError):
+            e0.acceptance_limit(synth.gen_prompt(cfg, 3, 20), 60, 33, 4, 3)          # block beyond the context's
+    finally:
+        e0.close()
+
+
 def test_repeated_forward_is_bit_identical_and_node_independent(setup):
     cfg, w, wg, eng = setup
     prompt = synth.gen_prompt(cfg, 5, 40)

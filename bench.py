@@ -148,6 +148,31 @@ def main():
             c1.record(stream)
             stream.synchronize()
             ceil_gbs = max(ceil_gbs, big.numel() * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9)
+        # ---- the gate/up GEMM's loads and nothing else: every work-group reads the whole activation matrix
+        # (L2) and its 1/256 of the weights (HBM, rotating through the 2 GiB buffer), one tile per CU
+        d_, F_ = cfg["d_model"], cfg["d_ffn"]
+        esz_ = 2 if cfg["dtype"] == "bf16" else 4
+        stepb = 1024 * 8 * 16                                    # whole steps for every variant below
+        sh_bytes = (nseq * (N + 1) * B * d_ * esz_) // stepb * stepb
+        pr_bytes = (2 * F_ * d_ * esz_ // 256) // stepb * stepb
+        load_only_us = None
+        if sh_bytes >= stepb and pr_bytes >= stepb and sh_bytes + 8 * 256 * pr_bytes <= big.numel():
+            load_only_us = {}
+            for threads, depth in ((512, 4), (512, 8), (1024, 8)):
+                def mixed(i):
+                    off = sh_bytes + (i % 8) * 256 * pr_bytes
+                    rc = eng.lib.ssd_debug_mixed_read(big.data_ptr(), sh_bytes, big.data_ptr() + off, pr_bytes, 256,
+                                                      threads, depth, sink.data_ptr(), stream.cuda_stream)
+                    assert rc == 0, rc
+                for i in range(4):
+                    mixed(i)
+                c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                c0.record(stream)
+                for i in range(16):
+                    mixed(i)
+                c1.record(stream)
+                stream.synchronize()
+                load_only_us[f"{threads}_lanes_x_{depth}_loads"] = c0.elapsed_time(c1) * 1e3 / 16
         del big
 
         # ---- per-kernel-class timing (HIP events on the same stream, separate pass)
@@ -256,6 +281,8 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic, "flops_per_launch": gu_flops, "achieved_GBs": gu_gbs, "us_per_launch": gu_us,
                 "launches_timed": gu["launches"], "us_per_launch_back_to_back_alone": gu_iso_us}
+    # a kernel that only loads this GEMM's bytes in the same one-tile-per-CU decomposition (no arithmetic)
+    roof["us_loads_alone_same_decomposition"] = load_only_us
     line = {
         "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
         "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

@@ -44,6 +44,16 @@ int ssd_k_accept(ssd_ctx* ctx, int n, const int* seqs, const int32_t* block_tok,
 int ssd_debug_stream_read(const void* src, size_t bytes, int work_groups, int waves_per_wg, int depth,
                           void* sink, void* hip_stream);
 
+/* The loads of a weight-streaming GEMM and nothing else: each of `work_groups` work-groups (512
+ * threads) reads all shared_bytes of `shared` (the activations every work-group needs) and its own
+ * priv_bytes_per_wg of `priv` (work-group g reads [g, g+1) * priv_bytes_per_wg: its share of the
+ * weights, non-temporal), evenly interleaved, with `threads` (512 or 1024) lanes and `depth` (4 or 8)
+ * 16-byte loads in flight per lane.  Both sizes must be multiples of threads * depth * 16 bytes; `priv`
+ * must hold work_groups * priv_bytes_per_wg bytes.  The duration is what the load path alone needs for
+ * that GEMM's bytes.  `sink` is 16 bytes of device scratch.  Asynchronous on `hip_stream`. */
+int ssd_debug_mixed_read(const void* shared, size_t shared_bytes, const void* priv, size_t priv_bytes_per_wg,
+                         int work_groups, int threads, int depth, void* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd
            "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
-           "ssd_debug_stream_read"]
+           "ssd_debug_stream_read", "ssd_debug_mixed_read"]
 LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
 
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
                                      C.POINTER(C.c_double)]
     lib.ssd_k_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
     lib.ssd_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.ssd_debug_mixed_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int,
+                                         C.c_void_p, C.c_void_p]
     lib.ssd_strerror.restype = C.c_char_p
     lib.ssd_strerror.argtypes = [C.c_int]
     lib.ssd_last_error.restype = C.c_char_p

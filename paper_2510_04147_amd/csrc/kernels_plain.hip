@@ -823,3 +823,55 @@ void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out,
 void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st) {
     k_int_to_float<<<(n + 255) / 256, 256, 0, st>>>(src, dst, n);
 }
+
+// ------------------------------------------------------------------------
+// Measurement aid: the loads of a weight-streaming GEMM and nothing else.  Every work-group reads
+// the SAME `shared` buffer once (the activations, served by L2) and its OWN slice of `priv` (its share
+// of the weights, from HBM, non-temporal like the GEMM's), interleaved evenly, 4 x 16 bytes in
+// flight per lane (DEPTH 4; or 8, and 512 or 1024 lanes).  Its duration is what the load path alone needs
+// for a GEMM's bytes in a one-tile-per-CU decomposition: the floor of such a kernel whatever its arithmetic costs.
+// ------------------------------------------------------------------------
+typedef unsigned int mr_u32x4 __attribute__((ext_vector_type(4)));
+template <int DEPTH, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_mixed_read(const mr_u32x4* __restrict__ shared, int steps_s,
+                                                        const mr_u32x4* __restrict__ priv, int steps_p, unsigned* sink) {
+    const int tid = threadIdx.x;
+    const mr_u32x4* pp = priv + (size_t)blockIdx.x * steps_p * DEPTH * THREADS;
+    unsigned acc = 0;
+    int ip = 0;
+    for (int is = 0; is < steps_s; ++is) {
+        mr_u32x4 v[DEPTH], w[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) v[d] = shared[((size_t)is * DEPTH + d) * THREADS + tid];
+        // private steps spread evenly over the shared ones: those whose index falls into this interval
+        const int hi = (int)(((long long)(is + 1) * steps_p) / steps_s);
+        for (; ip < hi; ++ip) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) w[d] = __builtin_nontemporal_load(&pp[((size_t)ip * DEPTH + d) * THREADS + tid]);
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) acc ^= w[d].x ^ w[d].y ^ w[d].z ^ w[d].w;
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;      // practically never true; keeps the loads alive
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_debug_mixed_read(const void* shared, size_t shared_bytes,
+                                                                           const void* priv, size_t priv_bytes_per_wg,
+                                                                           int work_groups, int threads, int depth,
+                                                                           void* sink, void* stream) {
+    if ((threads != 512 && threads != 1024) || (depth != 4 && depth != 8)) return SSD_EINVAL;
+    const size_t step = (size_t)threads * depth * 16;            // bytes one work-group reads per step
+    if (!shared || !priv || !sink || work_groups < 1 || shared_bytes < step || shared_bytes % step ||
+        priv_bytes_per_wg % step || shared_bytes / step > (1u << 20) || priv_bytes_per_wg / step > (1u << 20))
+        return SSD_EINVAL;
+    const int ss = (int)(shared_bytes / step), sp = (int)(priv_bytes_per_wg / step);
+    hipStream_t st = (hipStream_t)stream;
+    const mr_u32x4 *a = (const mr_u32x4*)shared, *b = (const mr_u32x4*)priv;
+    if (threads == 512 && depth == 4) k_mixed_read<4, 512><<<work_groups, 512, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
+    else if (threads == 512) k_mixed_read<8, 512><<<work_groups, 512, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
+    else if (depth == 4) k_mixed_read<4, 1024><<<work_groups, 1024, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
+    else k_mixed_read<8, 1024><<<work_groups, 1024, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
+}

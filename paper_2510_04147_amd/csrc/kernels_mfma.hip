@@ -634,7 +634,7 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
 // adds the partial sums in split order, applies the rotary embedding to its head's queries and to
 // the node's own keys and keeps the own key / value tile in LDS in fragment order.  For forwards whose
 // nodes have at most 32 rows (one query tile) and append nothing to the cache, head size 128.
-template <int DH, bool FUSED>
+template <int DH, bool FUSED, bool SUFFIX>
 __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* __restrict__ fw,
                                                                const bf16_t* __restrict__ q,
                                                                const bf16_t* __restrict__ kown,
@@ -702,12 +702,13 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     // Cache tiles are whole 32-position tiles of the cache; a tile may hold the end of the prefix and
     // the start of the suffix at once, tiles that lie inside the block are skipped, and every tile
     // listed holds at least one valid key.
-    const int blk_end = nd.S + nd.blen;
+    // (SUFFIX = false: a forward none of whose nodes has a suffix; the suffix terms fold away)
+    const int blk_end = nd.S + nd.blen, node_T = SUFFIX ? nd.T : 0;
     const int pre_tiles = (nd.S + 31) >> 5;
     const int suf_first = max(pre_tiles, blk_end >> 5);
-    const int suf_tiles = nd.T > blk_end ? max(((nd.T + 31) >> 5) - suf_first, 0) : 0;
+    const int suf_tiles = SUFFIX && node_T > blk_end ? max(((node_T + 31) >> 5) - suf_first, 0) : 0;
     const int cache_tiles = pre_tiles + suf_tiles, n_tiles = cache_tiles + ((nd.blen + 31) >> 5);
-    auto cache_tile = [&](int t) { return t < pre_tiles ? t : suf_first + (t - pre_tiles); };
+    auto cache_tile = [&](int t) { return !SUFFIX || t < pre_tiles ? t : suf_first + (t - pre_tiles); };
     // positions that are not keys of this node hold other or stale data: masked (keys) or zeroed (values)
     auto load_k = [&](bf16x8(&kf)[KST], int t) {
         const bf16_t* kp;
@@ -812,9 +813,9 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
         const int t0 = (own ? t - cache_tiles : cache_tile(t)) * 32;
         // keys t0 + [0, lim_a) and t0 + [lo_b, lim_b) of this tile exist
         const int lim_a = (own ? nd.blen : nd.S) - t0;
-        const int lo_b = own ? 32 : blk_end - t0, lim_b = own ? 0 : nd.T - t0;
-        auto valid = [&](int key) { return key < lim_a || (key >= lo_b && key < lim_b); };
-        const bool all_valid = lim_a >= 32 || (lo_b <= 0 && lim_b >= 32);
+        const int lo_b = own ? 32 : blk_end - t0, lim_b = own ? 0 : node_T - t0;
+        auto valid = [&](int key) { return key < lim_a || (SUFFIX && key >= lo_b && key < lim_b); };
+        const bool all_valid = lim_a >= 32 || (SUFFIX && lo_b <= 0 && lim_b >= 32);
         // ---- this wave's next tile, in flight while this one is processed
         if (t + ATTN_WAVES < n_tiles) {
             load_k(kn, t + ATTN_WAVES);
@@ -926,7 +927,7 @@ bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen) {
     return c->dm.dtype == SSD_BF16 && c->dm.dh == 128 && max_blen <= 32;
 }
 
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st) {
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, bool suffix, hipStream_t st) {
     const Dims& d = c->dm;
     dim3 grid(n_nodes * d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
@@ -935,15 +936,21 @@ bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, in
     c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown, (const bf16_t*)c->b.kcache, \
         (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale, \
         c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin
+#define SSD_ATTN_LAUNCH(DH_, FUSED_)                                                                       \
+    do {                                                                                                   \
+        if (suffix) k_attn_mfma<DH_, FUSED_, true><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);      \
+        else k_attn_mfma<DH_, FUSED_, false><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);            \
+    } while (0)
     if (n_part >= 0) {
         if (!attn_mfma_can_fuse_rope(c, max_blen)) return false;
-        k_attn_mfma<128, true><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+        SSD_ATTN_LAUNCH(128, true);
     } else if (d.dh == 128)
-        k_attn_mfma<128, false><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+        SSD_ATTN_LAUNCH(128, false);
     else if (d.dh == 64)
-        k_attn_mfma<64, false><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);
+        SSD_ATTN_LAUNCH(64, false);
     else
         return false;
+#undef SSD_ATTN_LAUNCH
 #undef SSD_ATTN_ARGS
     return true;
 }

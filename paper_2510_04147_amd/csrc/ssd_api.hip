@@ -439,10 +439,11 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
         return SSD_OK;
     }
     int max_blen = 0;
-    bool any_write_kv = false;
+    bool any_write_kv = false, any_suffix = false;
     for (int i = 0; i < hd.n_nodes; ++i) {
         max_blen = std::max(max_blen, hd.nodes[i].blen);
         any_write_kv |= hd.nodes[i].write_kv != 0;
+        any_suffix |= hd.nodes[i].T > hd.nodes[i].S + hd.nodes[i].blen;
     }
 
     // ---- the kernel sequence: a function of (M, ML, n_nodes, n_groups, max_blen, kernel path) only
@@ -470,7 +471,7 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
             {
                 ProfScope ps(c, KC_ATTN);
                 if (!(c->kernel_path >= 1 && d.dtype == SSD_BF16 &&
-                      launch_attn_mfma(c, hd.n_nodes, max_blen, l, fused ? ns : -1, st)))
+                      launch_attn_mfma(c, hd.n_nodes, max_blen, l, fused ? ns : -1, any_suffix, st)))
                     launch_attn_plain(c, M, l, st);
             }
             gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);
@@ -489,12 +490,13 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     };
 
     ssd_ctx::FwdGraph* fg = nullptr;
+    const int gflags = (any_write_kv ? 1 : 0) | (any_suffix ? 2 : 0);
     if (c->use_graphs && !c->profiling && st != nullptr) {      // the legacy default stream cannot be captured
         for (auto& g : c->graphs)
             if (g.M == M && g.ML == ML && g.n_nodes == hd.n_nodes && g.n_groups == hd.n_groups &&
-                g.max_blen == max_blen && g.kernel_path == c->kernel_path) { fg = &g; break; }
+                g.max_blen == max_blen && g.kernel_path == c->kernel_path && g.flags == gflags) { fg = &g; break; }
         if (!fg && c->graphs.size() < 64) {
-            c->graphs.push_back({M, ML, hd.n_nodes, hd.n_groups, max_blen, c->kernel_path, 0, nullptr});
+            c->graphs.push_back({M, ML, hd.n_nodes, hd.n_groups, max_blen, c->kernel_path, gflags, 0, nullptr});
             fg = &c->graphs.back();
         }
     }

@@ -189,6 +189,7 @@ struct ssd_ctx {
     int use_graphs;
     struct FwdGraph {
         int M, ML, n_nodes, n_groups, max_blen, kernel_path;
+        int flags;       // bit 0: some node appends KV, bit 1: some node reads a cached suffix (other kernels)
         int seen;
         hipGraphExec_t exec;
     };
@@ -248,5 +249,6 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
 int lm_tiles_mfma(int V);
 // n_part >= 0: the kernel also sums the QKV projection's n_part partial sums and applies the rotary
 // embedding itself (nodes of at most 32 rows, head size 128, no cache append); n_part < 0: q / kown / vown are ready
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, hipStream_t st);
+// suffix: some node of the forward sees cached positions behind its block (NodeDesc::T)
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, bool suffix, hipStream_t st);
 bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen);

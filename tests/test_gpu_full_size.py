@@ -18,7 +18,7 @@ def test_cfg2_full_depth():
     cfg = synth.model_config(wl["model"])
     wg = synth.gen_weights(cfg, 0, device="cuda")
     B, N, P = wl["block"], wl["draft"], wl["prompt_len"]
-    eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=P + 256, block=B, max_draft=N, max_rows=max(P, (N + 1) * B))
+    eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=P + 256, block=B, max_draft=N, max_rows=max(P + 2 * B, (N + 2) * B))
     prompt = synth.gen_prompt(cfg, wl["seed"], P)
     print("generate: stepwise and SSD, two blocks", flush=True)
     base, s0 = eng.generate([prompt], 2 * B, B, 0)
@@ -26,6 +26,22 @@ def test_cfg2_full_depth():
     assert np.array_equal(out, base), "GPU SSD differs from GPU stepwise at full depth"
     assert s0["forwards"] == 2 * B and s4["forwards"] <= 2 * B
     print("accept_hist", s4["accept_hist"][:N + 2], flush=True)
+    # the variants of the decoding loop at full depth: same tokens
+    eng.set_cross_block(1)
+    out_x, sx = eng.generate([prompt], 2 * B, B, N)
+    eng.set_cross_block(0)
+    assert np.array_equal(out_x, base) and sx["forwards"] <= s4["forwards"], "round across the block boundary"
+    eng.set_tree_mode(1)
+    out_m, _ = eng.generate([prompt], 2 * B, B, N)
+    eng.set_tree_mode(0)
+    assert np.array_equal(out_m, base), "mix-order tree"
+    # the dual cache is another model function: SSD against its own stepwise run (320-row refresh forwards)
+    eng.set_cache_mode(1, 8)
+    base_d, sd0 = eng.generate([prompt], 2 * B, B, 0)
+    out_d, sd4 = eng.generate([prompt], 2 * B, B, N)
+    eng.set_cache_mode(0)
+    assert np.array_equal(out_d, base_d) and sd0["kv_passes"] == sd4["kv_passes"] == 2 * B // 8
+    print("dual cache forwards", sd4["forwards"], "of", sd0["forwards"], flush=True)
     print("copying weights to the host for the oracle", flush=True)
     w = synth.weights_to(wg, "cpu")
     print("oracle: operand noise floor (4 layer-stack passes)", flush=True)

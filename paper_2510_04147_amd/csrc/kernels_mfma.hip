@@ -500,7 +500,7 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
     return true;
 }
 
-// Row tiles per pass: 1 (a stepwise forward of one block), 2, or 5 (a 5-node tree);
+// Row tiles per pass: 1 (a stepwise forward of one block), 2, 5 (a 5-node tree) or 6;
 // other row counts round up (padding rows are zero and never stored).
 template <int WN, int WK, int R, int EPI, int NCH>
 static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
@@ -515,10 +515,14 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
     if (mt == 5 && m_chunks > 1)
         return launch_one<WN, WK, R, 5, EPI, NCH, 32>(X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out,
                                                       m_chunks, st);
+    if (mt == 6 && m_chunks > 1)
+        return launch_one<WN, WK, R, 6, EPI, NCH, 32>(X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out,
+                                                      m_chunks, st);
     switch (mt) {
         SSD_MT_CASE(1)
         SSD_MT_CASE(2)
         SSD_MT_CASE(5)
+        SSD_MT_CASE(6)
     }
 #undef SSD_MT_CASE
     return false;
@@ -565,8 +569,11 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
     const int N = W.N, K = W.K;
     constexpr int WN = 4, WK = 2, KC = WK * 32;
     if (K % KC) return false;
-    // rows per pass: up to 160; more rows re-stream the weights per 160-row chunk
-    const int mt = M <= 32 ? 1 : M <= 64 ? 2 : 5;
+    // rows per pass: 32, 64 or 160 (a 5-node tree of 32-row blocks); forwards with more rows re-stream the
+    // weights once per pass, in passes of 160 or 192 rows, whichever needs fewer.  The rows of a pass share
+    // nothing but the weight fragments, so a row's sums do not depend on the choice.
+    int mt = M <= 32 ? 1 : M <= 64 ? 2 : 5;
+    if (M > 160 && (M + 191) / 192 < (M + 159) / 160) mt = 6;
     const int rows = mt * 32, m_chunks = (M + rows - 1) / rows;
     const bf16_t* x = (const bf16_t*)X;
     const uint4* wp = (const uint4*)W.packed;

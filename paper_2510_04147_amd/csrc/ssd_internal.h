@@ -247,6 +247,10 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
 bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, void* out, int M, int* n_split,
                       hipStream_t st);
 int lm_tiles_mfma(int V);
+// the fp32-partial-sum GEMMs (QKV, attention output, down), instantiated in a translation unit of their own;
+// mt row tiles of 32 rows per pass, m_chunks passes
+bool launch_gemm_mfma_f32(const ssd_ctx* c, const uint16_t* x, const uint4* wp, void* out, int M, int N, int K, int mt,
+                          int m_chunks, int* n_split, hipStream_t st);
 // n_part >= 0: the kernel also sums the QKV projection's n_part partial sums and applies the rotary
 // embedding itself (nodes of at most 32 rows, head size 128, no cache append); n_part < 0: q / kown / vown are ready
 // suffix: some node of the forward sees cached positions behind its block (NodeDesc::T)

@@ -49,3 +49,30 @@ def test_every_variant_equals_stepwise_on_random_shapes():
             assert np.array_equal(out, base_d) and st["tokens"] == gen * nseq, ("dual cache", case)
         finally:
             eng.close()
+
+
+def test_sixteen_sequences_at_once():
+    """The largest batch a context holds (16 slots): block boundaries, rounds across them and cache refreshes
+    of many sequences share forwards (up to three descriptor groups per sequence), and every sequence still
+    gets the tokens of its solo stepwise run."""
+    from paper_2510_04147_amd import binding
+    cfg = synth.model_config("tiny")
+    wg = synth.gen_weights(cfg, 0, device="cuda")
+    nseq, block, N, gen = 16, 8, 3, 24
+    plens = [5 + 3 * i for i in range(nseq)]
+    prompts = [synth.gen_prompt(cfg, 4000 + i, p) for i, p in enumerate(plens)]
+    eng = binding.SSD(cfg, wg, max_seqs=nseq, max_seq_len=max(plens) + gen + 8, block=block, max_draft=N,
+                      max_rows=max(nseq * (N + 2) * block, sum(p + gen for p in plens)))
+    try:
+        base = np.stack([eng.generate([p], gen, block, 0)[0][0] for p in prompts])
+        for cross in (0, 1):
+            eng.set_cross_block(cross)
+            out, st = eng.generate(prompts, gen, block, N)
+            assert np.array_equal(out, base) and st["tokens"] == nseq * gen, cross
+        eng.set_cross_block(0)
+        eng.set_cache_mode(1, 8)
+        base_d = np.stack([eng.generate([p], gen, block, 0)[0][0] for p in prompts])
+        out, st = eng.generate(prompts, gen, block, N)
+        assert np.array_equal(out, base_d) and st["kv_passes"] == nseq * gen // 8
+    finally:
+        eng.close()

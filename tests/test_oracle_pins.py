@@ -500,6 +500,18 @@ def test_ssd_with_dual_cache_is_token_identical_to_stepwise(tiny, refresh):
         assert st["forwards"] <= gen_len and (N > 0 or st["forwards"] == gen_len)
 
 
+def test_dual_cache_gqa_ragged_blocks_lossless():
+    """Grouped-query attention, a prompt and a generation length that fit no tile, a last block of 5."""
+    cfg = small_cfg()
+    w = synth.gen_weights(cfg, 3, std=0.2)
+    prompt = synth.gen_prompt(cfg, 5, 11)
+    for refresh in (3, 8):
+        ref, _ = decode.stepwise_dual(w, cfg, prompt, 21, 8, refresh)
+        for N in (1, 3, 5):
+            out, st = decode.ssd_dual(w, cfg, prompt, 21, 8, N, refresh)
+            assert out == ref, (refresh, N)
+
+
 @pytest.mark.parametrize("N,refresh,block", [(3, 8, 8), (4, 8, 8), (3, 4, 8), (4, 32, 32), (2, 16, 8)])
 def test_dual_cache_closed_form_with_zero_attention(tiny, N, refresh, block):
     """Zero attention output projections: no position sees any other, cached or not, every draft

@@ -217,6 +217,38 @@ def test_graph_replays_match_eager_launches(setup):
         eng.close()
 
 
+def test_graph_replays_keep_forwards_of_one_shape_but_other_kernels_apart(setup):
+    """Two sequences, rounds across the block boundary, the dual cache: forwards with the same numbers of
+    rows, nodes and groups differ in whether a node appends KV or reads a cached suffix, i.e. in the
+    kernels they launch.  With graphs on, every run must still equal the ungraphed one."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    p0, p1 = synth.gen_prompt(cfg, 61, 40), synth.gen_prompt(cfg, 62, 33)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=8, max_draft=3, max_rows=2 * (40 + 48))
+
+        def run():
+            outs = []
+            for cross, dual in ((0, 0), (1, 0), (0, 1), (1, 0), (0, 0)):
+                eng.set_cross_block(cross)
+                eng.set_cache_mode(dual, 8)
+                outs.append(eng.generate([p0, p1], 48, 8, 3)[0])
+            eng.set_cross_block(0)
+            eng.set_cache_mode(0)
+            return outs
+
+        try:
+            ref = run()
+            eng.set_graphs(1)
+            for rep in range(3):
+                for a, b in zip(ref, run()):
+                    assert np.array_equal(a, b), rep
+        finally:
+            eng.close()
+
+
 def test_generate_batch_of_two_ragged(setup):
     cfg, w, wg, eng = setup
     p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)

@@ -1,5 +1,5 @@
 """A small bf16 model with head size 64 and grouped-query attention (8 query / 2 KV heads, d = 512,
-FFN 1536, vocabulary 2048, 3 layers): the MFMA attention kernel's 64-channel instantiation, the
+FFN 1536, vocabulary 2080 = 65 tiles of 32, 3 layers): the MFMA attention kernel's 64-channel instantiation, the
 KV-head placement for head counts that are no multiple of 8, GEMMs with short K (8 and 24 chunks)
 and a narrow LM head, none of which the 8B / 7B shapes reach.  Teacher forced against the oracle
 with the bf16 tolerances, and every decoding variant against its stepwise run, bit for bit."""
@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 def test_head_size_64_gqa_bf16():
     from paper_2510_04147_amd import binding
     cfg = synth.model_config("tiny", dtype="bf16", n_layers=3, d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=64,
-                             d_ffn=1536, vocab=2048)
+                             d_ffn=1536, vocab=2080)     # 65 vocabulary tiles: the last LM-head work-group is partly empty
     wg = synth.gen_weights(cfg, 11, device="cuda", std=0.05)
     w = synth.weights_to(wg, "cpu")
     eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=32, max_draft=4, max_rows=2 * 8 * 32)

@@ -50,3 +50,34 @@ def test_head_size_64_gqa_bf16():
             assert np.array_equal(out, base_d), ("dual", blk)
     finally:
         eng.close()
+
+
+def test_shapes_that_do_not_tile_fall_back_per_projection():
+    """FFN width 1544 and vocabulary 2075 fit no MFMA tile: the gate/up, down and LM-head projections of this
+    bf16 model take the plain kernels while QKV and the attention output stay on the matrix cores, inside one
+    forward.  Same checks: the oracle teacher forced, and SSD against stepwise bit for bit."""
+    from paper_2510_04147_amd import binding
+    cfg = synth.model_config("tiny", dtype="bf16", n_layers=2, d_model=512, n_q_heads=8, n_kv_heads=4, head_dim=64,
+                             d_ffn=1544, vocab=2075)
+    wg = synth.gen_weights(cfg, 12, device="cuda", std=0.05)
+    w = synth.weights_to(wg, "cpu")
+    eng = binding.SSD(cfg, wg, max_seqs=1, max_seq_len=256, block=16, max_draft=3, max_rows=6 * 16 + 64)
+    try:
+        prompt = synth.gen_prompt(cfg, 23, 37)
+        sigma = parity_util.operand_noise_floor(cfg, w, prompt, 16, torch.float32)
+        tol = parity_util.bf16_tolerances(sigma)
+        ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 40, 16, 3, torch.float32, verbose=False, **tol)
+        print(f"sigma {sigma:.4f}", tot)
+        assert tot["forwards"] == st["forwards"] and tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
+        base, _ = eng.generate([prompt], 40, 16, 0)
+        for cross, dual in ((0, 0), (1, 0)):
+            eng.set_cross_block(cross)
+            out, _ = eng.generate([prompt], 40, 16, 3)
+            assert np.array_equal(out, base), cross
+        eng.set_cross_block(0)
+        eng.set_cache_mode(1, 8)
+        base_d, _ = eng.generate([prompt], 40, 16, 0)
+        out, _ = eng.generate([prompt], 40, 16, 3)
+        assert np.array_equal(out, base_d)
+    finally:
+        eng.close()

@@ -24,6 +24,11 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// exp through the hardware's base-2 exponential (relative error about 1e-6): the epilogues and the softmax
+// evaluate it once per output element, where the correctly rounded library routine costs as much as the
+// arithmetic it follows; the results are rounded to bf16 or summed over a vocabulary afterwards.
+__device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
+
 __device__ __forceinline__ uint16_t f2bf_m(float f) {
     uint32_t x = __float_as_uint(f);
     if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x40);
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
                                          acc[0][mt][(w + 2) * 4 + 2] + ou.z, acc[0][mt][(w + 2) * 4 + 3] + ou.w};
                     uint16_t o[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) o[j] = f2bf_m(gv[j] / (1.0f + expf(-gv[j])) * uv[j]);
+                    for (int j = 0; j < 4; ++j) o[j] = f2bf_m(gv[j] * __builtin_amdgcn_rcpf(1.0f + fast_exp(-gv[j])) * uv[j]);   // result rounded to bf16
                     const int m = m0 + mt * 32 + lm;
                     const int f = nt[0] * 16 + w * 8 + lh * 4;
                     if (m < M)
@@ -409,7 +414,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int n = nt[r] * 32 + (i >> 2) * 8 + lh * 4 + (i & 3);
-                    if (n != mask_id) se += expf(acc[r][mt][i] - bm);
+                    if (n != mask_id) se += fast_exp(acc[r][mt][i] - bm);
                 }
                 se += __shfl_xor(se, 32, 64);
                 const int m = m0 + mt * 32 + lm;

@@ -316,13 +316,13 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
         }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);
-        const float corr = expf(m_run - m_new);
+        const float corr = fast_exp(m_run - m_new);
         m_run = m_new;
         float psum = 0.f;
         bf16x8 pf[2];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float p = expf(sacc[i] - m_new);                  // 0 for masked keys
+            const float p = fast_exp(sacc[i] - m_new);                  // 0 for masked keys
             psum += p;
             pf[i >> 3][i & 7] = (__bf16)p;
         }
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
 #pragma unroll
     for (int w = 0; w < ATTN_WAVES; ++w) {
         const float mw = mrg[w][NE][lane];
-        cw[w] = mw == -INFINITY ? 0.f : expf(mw - m_all);            // a wave without a tile counts for nothing
+        cw[w] = mw == -INFINITY ? 0.f : fast_exp(mw - m_all);            // a wave without a tile counts for nothing
         l += mrg[w][NE + 1][lane] * cw[w];
     }
     l += __shfl_xor(l, 32, 64);

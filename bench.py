@@ -123,6 +123,28 @@ def main():
         torch.cuda.synchronize()
         ms_median = float(np.median([a.elapsed_time(b) for a, b in evs]))
 
+        # ---- what the gate/up GEMM costs inside the forward: the same forwards without its launches (their
+        # results are invalid, the other kernels and their order unchanged), alternating with full forwards so
+        # that drift cancels; two events per group of forwards, none around single kernels
+        def timed_group(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for _ in range(n):
+                step()
+            b.record(stream)
+            stream.synchronize()
+            return a.elapsed_time(b) / n
+        grp = max(2, args.steps // 4)
+        full_ms, skip_ms = [], []
+        for _ in range(4):
+            full_ms.append(timed_group(grp))
+            eng.lib.ssd_debug_skip_gate_up(eng.h, 1)
+            step()
+            skip_ms.append(timed_group(grp))
+            eng.lib.ssd_debug_skip_gate_up(eng.h, 0)
+            step()
+        gu_diff_us = (float(np.mean(full_ms)) - float(np.mean(skip_ms))) * 1e3 / cfg["n_layers"]
+
         if args.copy_calibration:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
             b = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -177,12 +199,14 @@ def main():
 
         # ---- per-kernel-class timing (HIP events on the same stream, separate pass)
         note(f"{ms_step:.3f} ms per forward; per-kernel event timing")
+        for _ in range(3):                   # the streaming tests above left caches and clocks in another state
+            step()
+        n_prof = max(6, args.steps // 2)
         eng.profile_begin()
-        for _ in range(max(3, args.steps // 5)):
+        for _ in range(n_prof):
             step()
         prof = eng.profile_read()
         eng.profile_end()
-        n_prof = max(3, args.steps // 5)
 
         # ---- the dominant kernel alone, for comparison: back to back through the kernel-level entry point,
         # one event pair around all launches; every layer's gate/up weights in turn, so the weights stream
@@ -269,7 +293,8 @@ def main():
     # An event pair around every launch serialises the launches and adds a few microseconds to each: the class
     # times of a forward add up to more than the forward takes untimed.  That excess, spread evenly over the
     # event pairs of a forward, is taken off the kernel's pair time (the result agrees with the kernel's duration
-    # in rocprofv3's trace of the same run within 1 %).
+    # in rocprofv3's trace of the same run within 1 %).  Reported next to it: what the forward gains when the
+    # kernel is left out (its duration plus its launch boundary and its effect on its neighbours).
     classes_ms = sum(v["ms"] for v in prof.values()) / n_prof
     pairs_per_forward = sum(v["launches"] for v in prof.values()) / n_prof
     event_pair_us = max(0.0, (classes_ms - ms_step) * 1e3 / pairs_per_forward) if pairs_per_forward > 0 else 0.0
@@ -283,13 +308,15 @@ def main():
         roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "us_per_launch_with_event_pairs": gu_us_raw,
+                "us_per_launch_by_leaving_it_out": gu_diff_us,
                 "event_pair_overhead_us": event_pair_us, "launches_timed": gu["launches"],
                 "us_per_launch_back_to_back_alone": gu_iso_us}
     else:
         roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "mfma", "achieved": gu_tflops,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic, "flops_per_launch": gu_flops, "achieved_GBs": gu_gbs, "us_per_launch": gu_us,
-                "us_per_launch_with_event_pairs": gu_us_raw, "event_pair_overhead_us": event_pair_us,
+                "us_per_launch_with_event_pairs": gu_us_raw,
+                "us_per_launch_by_leaving_it_out": gu_diff_us, "event_pair_overhead_us": event_pair_us,
                 "launches_timed": gu["launches"], "us_per_launch_back_to_back_alone": gu_iso_us}
     # a kernel that only loads this GEMM's bytes in the same one-tile-per-CU decomposition (no arithmetic)
     roof["us_loads_alone_same_decomposition"] = load_only_us

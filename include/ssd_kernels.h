@@ -44,6 +44,13 @@ int ssd_k_accept(ssd_ctx* ctx, int n, const int* seqs, const int32_t* block_tok,
 int ssd_debug_stream_read(const void* src, size_t bytes, int work_groups, int waves_per_wg, int depth,
                           void* sink, void* hip_stream);
 
+/* Measurement aid: while on (1), every forward of the context leaves out the gate/up GEMM launch of each
+ * layer (the feed-forward block then reads stale activations: the results of such forwards are invalid, their
+ * kernels and launch order otherwise unchanged).  The difference between the duration of a forward with and
+ * without it, divided by the layer count, is what one gate/up launch costs inside the forward, measured with
+ * two events per forward instead of two per kernel.  Returns the previous setting or an error. */
+int ssd_debug_skip_gate_up(ssd_ctx* ctx, int on);
+
 /* The loads of a weight-streaming GEMM and nothing else: each of `work_groups` work-groups (512
  * threads) reads all shared_bytes of `shared` (the activations every work-group needs) and its own
  * priv_bytes_per_wg of `priv` (work-group g reads [g, g+1) * priv_bytes_per_wg: its share of the

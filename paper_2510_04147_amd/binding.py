@@ -23,7 +23,7 @@ EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd
            "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
-           "ssd_debug_stream_read", "ssd_debug_mixed_read"]
+           "ssd_debug_stream_read", "ssd_debug_mixed_read", "ssd_debug_skip_gate_up"]
 LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
 
@@ -81,6 +81,7 @@ def load_library() -> C.CDLL:
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cross_block.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cache_mode.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    lib.ssd_debug_skip_gate_up.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_acceptance_limit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ssd_refresh_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,

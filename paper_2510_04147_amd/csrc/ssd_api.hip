@@ -191,6 +191,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->tree_mode = 0;
     c->cross_block = 0;
     c->cache_mode = 0;
+    c->debug_skip_gate_up = 0;
     c->refresh_interval = 0;
     memset(c->total_len, 0, sizeof c->total_len);
     c->use_graphs = 0;
@@ -296,6 +297,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_cache_mode(ssd_ctx
     return old;
 }
 
+extern "C" __attribute__((visibility("default"))) int ssd_debug_skip_gate_up(ssd_ctx* c, int on) {
+    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
+    const int old = c->debug_skip_gate_up;
+    c->debug_skip_gate_up = on;
+    return old;
+}
+
 extern "C" __attribute__((visibility("default"))) int ssd_set_tree_mode(ssd_ctx* c, int mode) {
     if (!c || (mode != 0 && mode != 1)) return SSD_EINVAL;
     const int old = c->tree_mode;
@@ -391,6 +399,7 @@ struct Upload {           // block state to push before the forward (stateless A
 static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void* out, int M, int* n_split) {
     ProfScope ps(c, cls);
     *n_split = 1;
+    if (cls == KC_GEMM_GU && c->debug_skip_gate_up) return;       // measurement aid, see ssd_debug_skip_gate_up
     if (c->kernel_path >= 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, n_split, c->stream))
         return;
     const int N = epi == EPI_SWIGLU ? W.N / 2 : W.N;

@@ -197,6 +197,7 @@ struct ssd_ctx {
     // Cache of the paper's experiments (Section 4.1), 0 = exact block-causal prefix cache: 1 = dual
     // cache, keys and values of ALL positions renewed by a full forward every refresh_interval
     // decoded tokens (0 = once per block).  total_len[seq] > 0: positions up to there are cached.
+    int debug_skip_gate_up;  // measurement aid: forwards leave out the gate/up GEMM (their results are invalid)
     int cache_mode, refresh_interval;
     int total_len[SSD_MAX_SEQS];
     int cached_len[SSD_MAX_SEQS];

@@ -26,6 +26,22 @@ extern "C" {
  * Asynchronous on the context's stream.  Errors: SSD_EINVAL, SSD_ERANGE. */
 int ssd_k_linear(ssd_ctx* ctx, int which, int layer, const void* x, int M, void* out);
 
+/* SSD_LIN_LM of ssd_k_linear for callers that cannot allocate device memory or hand over a region
+ * for partial results of their own: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The per-tile partial results of the LM-head reduction and the integer
+ * arg-max live in a static device array of SSD_STATIC_SCRATCH_BYTES that each GPU the library runs
+ * on holds until the process ends (its address is resolved once per device in ssd_create); the call
+ * itself allocates nothing and uses nothing of the context's workspace but the weights.
+ *   x   device, cfg.dtype [M, d_model], row-major        out  device, fp32 [3, M] as for SSD_LIN_LM
+ * Same kernels, same results as ssd_k_linear(ctx, SSD_LIN_LM, 0, x, M, out).  M * ceil(vocab / 32)
+ * * 12 + M * 4 bytes must fit the array (M <= 176 for a 126464-token vocabulary), else SSD_ERANGE and
+ * nothing is launched.  Nothing in the array has to start at zero: every entry that is read was
+ * written by the same call.  All calls on one GPU share that GPU's array, from every context and
+ * stream: calls that overlap in time on one GPU race; on one stream they are ordered.
+ * Asynchronous on the context's stream.  Errors: SSD_EINVAL, SSD_ERANGE, SSD_EHIP. */
+#define SSD_STATIC_SCRATCH_BYTES (8u << 20)
+int ssd_k_lm_head_static(ssd_ctx* ctx, const void* x, int M, void* out);
+
 /* The acceptance step alone (Section 3.2.4; with ssd_set_tree_mode(ctx, 1) the mix-order walk of
  * Section 5.2) on caller-supplied model outputs.  Arguments as ssd_verify_tree, without prefix
  * lengths; row_conf / row_argmax are device arrays with one entry per row of the forward the call

@@ -22,7 +22,7 @@ EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_graphs", "ssd_set_tree_mode", "ssd_set_cross_block",
            "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
-           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept",
+           "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept", "ssd_k_lm_head_static",
            "ssd_debug_stream_read", "ssd_debug_mixed_read", "ssd_debug_skip_gate_up"]
 LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
@@ -91,6 +91,7 @@ def load_library() -> C.CDLL:
     lib.ssd_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
     lib.ssd_k_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    lib.ssd_k_lm_head_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
     lib.ssd_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     lib.ssd_debug_mixed_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int,
                                          C.c_void_p, C.c_void_p]
@@ -324,6 +325,11 @@ class SSD:
         """One linear step on caller-supplied rows x [M, K] (device tensor of the model dtype)."""
         assert x.is_contiguous() and out.is_contiguous() and x.device == self.device
         self._chk(self.lib.ssd_k_linear(self.h, which, layer, x.data_ptr(), x.shape[0], out.data_ptr()))
+
+    def k_lm_head_static(self, x, out):
+        """The LM-head reduction of k_linear(LIN_LM, ...) with its partial results in the library's static array."""
+        assert x.is_contiguous() and out.is_contiguous() and x.device == self.device
+        self._chk(self.lib.ssd_k_lm_head_static(self.h, x.data_ptr(), x.shape[0], out.data_ptr()))
 
     def profile_begin(self):
         self._chk(self.lib.ssd_profile_begin(self.h))

@@ -769,8 +769,12 @@ void launch_gemm_plain(const ssd_ctx* c, int epi, const void* X, const void* W, 
 int lm_tiles_plain(int V) { return (V + PBN - 1) / PBN; }
 
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st) {
-    k_lm_merge<<<M, 256, 0, st>>>(c->b.lm_part, n_tiles, c->b.row_max, c->b.row_arg, c->b.row_conf, c->dm.V,
-                                 c->dm.mask_id);
+    launch_lm_merge_to(c, M, n_tiles, c->b.lm_part, c->b.row_max, c->b.row_arg, c->b.row_conf, st);
+}
+
+void launch_lm_merge_to(const ssd_ctx* c, int M, int n_tiles, const float* part, float* row_max, int* row_arg,
+                        float* row_conf, hipStream_t st) {
+    k_lm_merge<<<M, 256, 0, st>>>(part, n_tiles, row_max, row_arg, row_conf, c->dm.V, c->dm.mask_id);
 }
 
 void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st) {

@@ -34,6 +34,27 @@ static void set_err(ssd_ctx* c, const char* fmt, ...) {
 
 static thread_local std::string g_create_err;
 
+// ------------------------------------------------------------------ static scratch
+// Device memory of the allocation-free entry point (ssd_k_lm_head_static): one array per GPU the
+// library runs on, held until the process ends.  `scratch` is a host-side stand-in for the symbol;
+// the device address comes from hipGetSymbolAddress, once per device, and only that pointer is
+// ever handed to kernels or copies.
+static __device__ __align__(256) unsigned char scratch[SSD_STATIC_SCRATCH_BYTES];
+#define SSD_MAX_DEVICES 64
+static void* g_scratch_ptr[SSD_MAX_DEVICES];          // per device, nullptr until resolved
+
+// Resolves the array's address on `device` (which must be the current device).
+static hipError_t resolve_scratch(int device) {
+    if (device < 0 || device >= SSD_MAX_DEVICES) return hipErrorInvalidDevice;
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+    return hipSuccess;
+}
+
 extern "C" __attribute__((visibility("default"))) const char* ssd_strerror(int code) {
     switch (code) {
         case SSD_OK: return "ok";
@@ -167,6 +188,18 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     carve(d, (char*)workspace, &c->b);
     c->stream = (hipStream_t)hip_stream;
     c->part_cols = d.nqkv() > d.d ? d.nqkv() : d.d;
+    c->device = -1;
+    {
+        // the context lives on the current device; the static scratch array of that device is
+        // resolved here, at set-up, so that the allocation-free entry point only looks it up
+        hipError_t e0 = hipGetDevice(&c->device);
+        if (e0 == hipSuccess) e0 = resolve_scratch(c->device);
+        if (e0 != hipSuccess) {
+            g_create_err = std::string("static scratch: ") + hipGetErrorString(e0);
+            delete c;
+            return SSD_EHIP;
+        }
+    }
     // weights: keep the caller's pointers, and repack what tiles into MFMA fragment order
     {
         char* pk = (char*)c->b.packed;
@@ -1064,6 +1097,38 @@ extern "C" __attribute__((visibility("default"))) int ssd_k_accept(ssd_ctx* c, i
     if (!n_draft || !row_conf || !row_argmax) { set_err(c, "ssd_k_accept: null argument"); return SSD_EINVAL; }
     return step_common(c, "ssd_k_accept", n, seqs, block_tok, masked, nullptr, block_len, draft_pos, draft_tok, n_draft,
                        n_draft_next, out, row_conf, row_argmax);
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_k_lm_head_static(ssd_ctx* c, const void* x, int M,
+                                                                           void* out) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!x || !out || M < 1) { set_err(c, "k_lm_head_static: null pointer or M < 1"); return SSD_EINVAL; }
+    // per-tile partials [M, tiles, 3] fp32, then the rows' arg-max as integers [M]; the finest tiling of
+    // any kernel path bounds the tile count
+    const size_t tiles_max = (size_t)lm_tiles_for(d);
+    const size_t part_bytes = (((size_t)M * tiles_max * 3 * 4) + 255) & ~(size_t)255;
+    const size_t need = part_bytes + (size_t)M * 4;
+    if (M > d.max_rows || need > SSD_STATIC_SCRATCH_BYTES) {
+        set_err(c, "k_lm_head_static: %d rows of a %d-token vocabulary need %zu bytes of scratch, the static array holds %u",
+                M, d.V, need, (unsigned)SSD_STATIC_SCRATCH_BYTES);
+        return SSD_ERANGE;
+    }
+    void* sp = c->device >= 0 && c->device < SSD_MAX_DEVICES ? g_scratch_ptr[c->device] : nullptr;
+    if (!sp) { set_err(c, "k_lm_head_static: the static scratch of device %d was never resolved", c->device); return SSD_EHIP; }
+    float* part = (float*)sp;
+    int* row_arg = (int*)((char*)sp + part_bytes);
+    float* o = (float*)out;
+    int tiles = 1;
+    if (!(c->kernel_path >= 1 && d.dtype == SSD_BF16 &&
+          launch_gemm_mfma(c, EPI_LMHEAD, x, c->lm_head, part, M, &tiles, c->stream))) {
+        tiles = lm_tiles_plain(d.V);
+        launch_gemm_plain(c, EPI_LMHEAD, x, c->lm_head.raw, part, M, d.V, d.d, c->stream);
+    }
+    launch_lm_merge_to(c, M, tiles, part, o, row_arg, o + 2 * (size_t)M, c->stream);
+    launch_int_to_float(row_arg, o + M, M, c->stream);
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
 }
 
 extern "C" __attribute__((visibility("default"))) int ssd_k_linear(ssd_ctx* c, int which, int layer, const void* x,

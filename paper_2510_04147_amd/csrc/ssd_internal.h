@@ -179,6 +179,7 @@ struct ssd_ctx {
     const float* final_norm;
     int part_cols;             // columns of one split-K partial buffer = max(d, nqkv)
     hipStream_t stream;
+    int device;                // HIP device the context was created on
     int kernel_path;
     int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
     int tree_mode;       // 0 = greedy chain (Section 3.2.3), 1 = mix-order tree (Section 5.2)
@@ -230,6 +231,9 @@ void launch_rope(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_p
 void launch_attn_plain(const ssd_ctx* c, int M, int layer, hipStream_t st);
 void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st);
 void launch_lm_merge(const ssd_ctx* c, int M, int n_tiles, hipStream_t st);
+// the same merge on caller-chosen buffers: part [M, n_tiles, 3] -> row_max / row_arg / row_conf [M]
+void launch_lm_merge_to(const ssd_ctx* c, int M, int n_tiles, const float* part, float* row_max, int* row_arg,
+                        float* row_conf, hipStream_t st);
 int lm_tiles_plain(int V);
 // out[M,N] = sum over the first n_part split-K partial buffers, in split order
 void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out, hipStream_t st);

@@ -30,17 +30,33 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0        # dense bf16
 
 
+def kernel_source_stamp():
+    """Hash of the sources the GEMM kernels are built from: a counter summary under profiles/ names the
+    stamp of the build it was taken with, and is only quoted while the sources still hash to it."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("gemm_mfma.h", "kernels_mfma.hip", "kernels_mfma_f32.hip"):
+        h.update(open(os.path.join(ROOT, "paper_2510_04147_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_measured_traffic(workload):
     """HBM bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), or None."""
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size).  Returns (bytes or None, note):
+    None when there is no summary or when it was taken with other kernel sources than the present ones."""
     path = os.path.join(ROOT, "profiles", f"gemm_gate_up_{workload}_traffic.txt")
+    traffic, stamp = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                traffic = float(line.split(":", 1)[1])
+            if line.startswith("kernel_source_stamp:"):
+                stamp = line.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "no counter summary for this workload"
+    if stamp != kernel_source_stamp():
+        return None, f"counter summary is stale (taken at kernel sources {stamp}, now {kernel_source_stamp()})"
+    return traffic, "profiles/" + os.path.basename(path)
 
 
 def main():
@@ -69,6 +85,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
+    mlib = binding.load_measure_library()
     over = {"n_layers": args.layers} if args.layers else {}
     cfg = synth.model_config(wl["model"], **over)
     B, N, P, G, nseq = wl["block"], wl["draft"], wl["prompt_len"], wl["gen_len"], wl["batch"]
@@ -123,28 +140,6 @@ def main():
         torch.cuda.synchronize()
         ms_median = float(np.median([a.elapsed_time(b) for a, b in evs]))
 
-        # ---- what the gate/up GEMM costs inside the forward: the same forwards without its launches (their
-        # results are invalid, the other kernels and their order unchanged), alternating with full forwards so
-        # that drift cancels; two events per group of forwards, none around single kernels
-        def timed_group(n):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            for _ in range(n):
-                step()
-            b.record(stream)
-            stream.synchronize()
-            return a.elapsed_time(b) / n
-        grp = max(2, args.steps // 4)
-        full_ms, skip_ms = [], []
-        for _ in range(4):
-            full_ms.append(timed_group(grp))
-            eng.lib.ssd_debug_skip_gate_up(eng.h, 1)
-            step()
-            skip_ms.append(timed_group(grp))
-            eng.lib.ssd_debug_skip_gate_up(eng.h, 0)
-            step()
-        gu_diff_us = (float(np.mean(full_ms)) - float(np.mean(skip_ms))) * 1e3 / cfg["n_layers"]
-
         if args.copy_calibration:
             a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
             b = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -162,11 +157,11 @@ def main():
         ceil_gbs = 0.0
         for wgs, depth in ((256, 8), (512, 8), (1024, 16)):
             for _ in range(2):
-                eng.lib.ssd_debug_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
+                mlib.ssd_measure_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
             c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             c0.record(stream)
             for _ in range(5):
-                eng.lib.ssd_debug_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
+                mlib.ssd_measure_stream_read(big.data_ptr(), big.numel(), wgs, 8, depth, sink.data_ptr(), stream.cuda_stream)
             c1.record(stream)
             stream.synchronize()
             ceil_gbs = max(ceil_gbs, big.numel() * 5 / (c0.elapsed_time(c1) * 1e-3) / 1e9)
@@ -183,7 +178,7 @@ def main():
             for threads, depth in ((512, 4), (512, 8), (1024, 8)):
                 def mixed(i):
                     off = sh_bytes + (i % 8) * 256 * pr_bytes
-                    rc = eng.lib.ssd_debug_mixed_read(big.data_ptr(), sh_bytes, big.data_ptr() + off, pr_bytes, 256,
+                    rc = mlib.ssd_measure_mixed_read(big.data_ptr(), sh_bytes, big.data_ptr() + off, pr_bytes, 256,
                                                       threads, depth, sink.data_ptr(), stream.cuda_stream)
                     assert rc == 0, rc
                 for i in range(4):
@@ -276,6 +271,35 @@ def main():
                                 ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0))),
                 acceptance_limit=dict(draft_length=N, reduction_top_k=[round(x, 4) for x in lim["reduction"]],
                                       upper_bound=N / (N + 1), rounds=lim["rounds"]))
+            # ---- the other acceptance extreme: the same model with every attention output projection zeroed.
+            # A position's logits then depend on its own token only, all masked positions tie, the order is left
+            # to right and every draft verifies: each round accepts N + 1 tokens (the upper bound of Tables 2-3).
+            # Random weights sit near the lower extreme (about 1.3 tokens per forward); a trained model lies between.
+            note("zero-attention model: generation at the upper acceptance bound")
+            eng.close()
+            wz = {k: v for k, v in wg.items() if k != "layers"}
+            wz["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in wg["layers"]]
+            engz = binding.SSD(cfg, wz, max_seqs=nseq, max_seq_len=P + G, block=B, max_draft=N,
+                               max_rows=max(P, nseq * (N + 1) * B))
+            engz.generate(prompts, B, B, N)                      # warm
+            toks_z, st_z = engz.generate(prompts, G, B, N)
+            toks_z0, st_z0 = engz.generate(prompts, G, B, 0)
+            engz.close()
+            del wz, engz
+            hist_z = st_z["accept_hist"]
+            full_rounds = hist_z[N + 1]
+            gen["zero_attention"] = dict(
+                ssd_tokens_per_s=GT / (st_z["total_ms"] / 1e3), stepwise_tokens_per_s=GT / (st_z0["total_ms"] / 1e3),
+                ssd_forwards=st_z["forwards"], stepwise_forwards=st_z0["forwards"],
+                accepted_per_forward=GT / max(sum(hist_z), 1), accept_hist=hist_z[:N + 2],
+                ssd_decode_ms_per_forward=st_z["decode_ms"] / st_z["forwards"],
+                stepwise_ms_per_forward=st_z0["decode_ms"] / st_z0["forwards"],
+                ssd_equals_stepwise=bool(np.array_equal(toks_z, toks_z0)))
+            # closed form: per block one draft forward and ceil((B - 1) / (N + 1)) verification rounds
+            blocks = -(-G // B)
+            want_fwd = sum(1 + -(-(min(B, G - b * B) - 1) // (N + 1)) for b in range(blocks))
+            gen["zero_attention"]["forwards_closed_form"] = want_fwd
+            gen["zero_attention"]["full_depth_rounds"] = full_rounds
 
     # ---- roofline arithmetic
     M = nseq * (N + 1) * B
@@ -293,22 +317,20 @@ def main():
     # An event pair around every launch serialises the launches and adds a few microseconds to each: the class
     # times of a forward add up to more than the forward takes untimed.  That excess, spread evenly over the
     # event pairs of a forward, is taken off the kernel's pair time (the result agrees with the kernel's duration
-    # in rocprofv3's trace of the same run within 1 %).  Reported next to it: what the forward gains when the
-    # kernel is left out (its duration plus its launch boundary and its effect on its neighbours).
+    # in rocprofv3's trace of the same run within 1 %).
     classes_ms = sum(v["ms"] for v in prof.values()) / n_prof
     pairs_per_forward = sum(v["launches"] for v in prof.values()) / n_prof
     event_pair_us = max(0.0, (classes_ms - ms_step) * 1e3 / pairs_per_forward) if pairs_per_forward > 0 else 0.0
     gu_us = max(gu_us_raw - event_pair_us, 0.0)
     gu_gbs = gu_bytes / (gu_us * 1e-6) / 1e9 if gu_us > 0 else 0.0
     gu_tflops = gu_flops / (gu_us * 1e-6) / 1e12 if gu_us > 0 else 0.0
-    traffic = read_measured_traffic(args.workload)
+    traffic, traffic_note = read_measured_traffic(args.workload)
     # the bound is whichever of the two rooflines takes longer for this kernel's bytes and flops
     hbm_bound = gu_bytes / (HBM_PEAK_GBS * 1e9) >= gu_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
     if hbm_bound:
         roof = {"kernel": "k_gemm_mfma<SwiGLU> (gate/up projection)", "bound": "hbm", "achieved": gu_gbs,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": traffic,
                 "bytes_per_launch": gu_bytes, "us_per_launch": gu_us, "us_per_launch_with_event_pairs": gu_us_raw,
-                "us_per_launch_by_leaving_it_out": gu_diff_us,
                 "event_pair_overhead_us": event_pair_us, "launches_timed": gu["launches"],
                 "us_per_launch_back_to_back_alone": gu_iso_us}
     else:
@@ -316,10 +338,14 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gu_tflops / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": traffic, "flops_per_launch": gu_flops, "achieved_GBs": gu_gbs, "us_per_launch": gu_us,
                 "us_per_launch_with_event_pairs": gu_us_raw,
-                "us_per_launch_by_leaving_it_out": gu_diff_us, "event_pair_overhead_us": event_pair_us,
+                "event_pair_overhead_us": event_pair_us,
                 "launches_timed": gu["launches"], "us_per_launch_back_to_back_alone": gu_iso_us}
     # a kernel that only loads this GEMM's bytes in the same one-tile-per-CU decomposition (no arithmetic)
     roof["us_loads_alone_same_decomposition"] = load_only_us
+    roof["traffic_source"] = traffic_note
+    # the whole forward against the same peak: its algorithmic bytes (weights + prefix KV) over its duration
+    roof["forward_achieved"] = fwd_gbs if hbm_bound else fwd_tflops
+    roof["forward_frac"] = fwd_gbs / HBM_PEAK_GBS if hbm_bound else fwd_tflops / MFMA_BF16_PEAK_TFLOPS
     line = {
         "metric": "generated tokens/sec at batch 1 + verify-forward HBM GB/s (% of roofline)",
         "value": gen.get("ssd_tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -339,6 +365,18 @@ def main():
     }
     if args.layers:
         line["invalid"] = "layer count overridden"
+    # a run whose SSD tokens differ from stepwise decoding measures a broken path: say so and fail
+    broken = []
+    if gen:
+        if not gen["ssd_equals_stepwise"]:
+            broken.append("SSD / mix-order / cross-block tokens differ from stepwise decoding")
+        if not gen["dual_cache"]["ssd_equals_stepwise"]:
+            broken.append("dual cache: SSD tokens differ from stepwise decoding")
+        za = gen["zero_attention"]
+        if not za["ssd_equals_stepwise"] or za["ssd_forwards"] != za["forwards_closed_form"]:
+            broken.append("zero-attention model: tokens differ from stepwise or forwards differ from the closed form")
+    if broken:
+        line["invalid"] = "; ".join(broken)
 
     # ---- CPU oracle on a bounded sample (reported baseline, never a target)
     if not args.no_cpu_baseline:
@@ -358,6 +396,8 @@ def main():
                                           f"on the same {cfg['n_layers']}-layer model: {n_pre}-token prefill, one "
                                           f"{nb}-position block = {st['forwards']} forwards + {st['kv_passes']} KV passes"}
     print(json.dumps(line))
+    if broken:
+        sys.exit(3)
 
 
 if __name__ == "__main__":

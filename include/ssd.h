@@ -123,8 +123,8 @@ size_t ssd_workspace_bytes(const ssd_config* cfg);
 
 /* Create a context.  `workspace` is device memory of at least ssd_workspace_bytes(cfg),
  * 256-byte aligned; `hip_stream` is a hipStream_t (NULL = the default stream).
- * The weights must be completely written before the call: bf16 weights are
- * repacked into the workspace by kernels on `hip_stream`.
+ * bf16 weights are repacked into the workspace by kernels on `hip_stream`; the call first waits
+ * for the device (hipDeviceSynchronize), so weights written on any stream of it are complete.
  * Errors: SSD_EINVAL (null / inconsistent config), SSD_ERANGE (block, draft,
  * d_model or head_dim beyond the supported limits), SSD_ENOMEM, SSD_EHIP. */
 int ssd_create(const ssd_config* cfg, const ssd_weights* weights, void* workspace,
@@ -252,10 +252,12 @@ int ssd_refresh_kv(ssd_ctx* ctx, int seq, const int32_t* tokens, int total_len, 
  * entries): matched[k-1] = tokens with rank < k, i.e. found among the k best candidates a draft made
  * at the round's start would hold; forwards[k-1] = sum over rounds of (steps - matched + 1), the
  * forwards an ideal verification tree would need; 1 - forwards / gen_len is the table's reduction,
- * n_draft / (n_draft + 1) its upper bound.  *rounds (optional) = number of rounds; out_tokens
- * (optional, host, gen_len entries) = the decoded tokens.  Synchronous.  Errors as ssd_generate. */
+ * n_draft / (n_draft + 1) its upper bound; reduction[k-1] (optional, host, k_max entries) receives
+ * 1 - forwards[k-1] / gen_len.  *rounds (optional) = number of rounds; out_tokens (optional, host,
+ * gen_len entries) = the decoded tokens.  Synchronous.  Errors as ssd_generate. */
 int ssd_acceptance_limit(ssd_ctx* ctx, const int32_t* prompt, int prompt_len, int gen_len, int block, int n_draft,
-                         int k_max, int32_t* out_tokens, int64_t* matched, int64_t* forwards, int64_t* rounds);
+                         int k_max, int32_t* out_tokens, int64_t* matched, int64_t* forwards, int64_t* rounds,
+                         double* reduction);
 
 /* Shape of the verification tree of ssd_verify_tree / ssd_generate:
  * 0 = the greedy chain of n_draft + 1 nodes (Section 3.2.3), 1 = the mix-order

@@ -1,6 +1,6 @@
 /*
  * ssd_kernels.h - kernel-level entry points of the SSD library, for unit
- * parity tests and measurement.  They run exactly the kernels the forward
+ * parity tests.  They run exactly the kernels the forward
  * (ssd.h) runs for one step of Section 3.1's transformer f_theta, on operands
  * the caller supplies, so a single step can be checked against a definition
  * with nothing upstream to blur it.
@@ -25,6 +25,38 @@ extern "C" {
  * Split-K partial sums are added in split order, as the forward's consumers do.
  * Asynchronous on the context's stream.  Errors: SSD_EINVAL, SSD_ERANGE. */
 int ssd_k_linear(ssd_ctx* ctx, int which, int layer, const void* x, int M, void* out);
+
+/* One node of a kernel-level attention call: rows [sum of earlier blen, +blen) of the call belong to
+ * sequence slot `seq`, sit at positions [S, S + blen) and attend to the slot's cached positions
+ * [0, S), to their own node's rows and, if T > S + blen, to the cached positions [S + blen, T)
+ * (the dual cache of Section 4.1); T = 0: no cached suffix. */
+typedef struct { int seq, S, blen, T; } ssd_k_node;
+
+/* Writes caller-supplied keys and values into the cache of sequence slot `seq`, layer `layer`, at
+ * positions [pos0, pos0 + n): k, v device, cfg.dtype, row-major [n, n_kv_heads, head_dim], keys
+ * already rotated.  The slot's cached length (ssd_cached_len) is not changed: the kernel-level
+ * attention call names the prefix length itself.  Asynchronous.  Errors: SSD_EINVAL, SSD_ERANGE. */
+int ssd_k_write_cache(ssd_ctx* ctx, int seq, int layer, int pos0, int n, const void* k, const void* v);
+
+/* The attention step of layer `layer` (Section 3.1's f_theta restricted to the scope of Eq. 5: cached
+ * prefix + the node's own rows, bidirectional) with exactly the kernels the forward runs, on a
+ * caller-supplied QKV projection: qkv device fp32 [n_part, M, (Hq + 2 Hkv) * dh], the projection's
+ * split-K partial sums (added in split order; n_part = 1: the projection itself), M = sum of the
+ * nodes' blen, `nodes` a host array.  fused = 0: the rotary stage runs as a kernel of its own, then
+ * the attention kernel of the context's kernel path; out_q (cfg.dtype [M, Hq * dh]) and out_k / out_v
+ * (cfg.dtype [M, Hkv, dh]; both or neither) optionally receive the rotary stage's outputs, i.e. the
+ * attention kernel's operands.  fused = 1: the attention kernel sums, rotates and converts itself
+ * (bf16, kernel path 1, head size 128, nodes of at most 32 rows; out_q / out_k / out_v must be
+ * NULL).  out_attn: cfg.dtype [M, Hq * dh].  Nothing is appended to the cache.  Asynchronous.
+ * Errors: SSD_EINVAL, SSD_ERANGE. */
+int ssd_k_attention(ssd_ctx* ctx, int layer, int n_nodes, const ssd_k_node* nodes, const float* qkv, int n_part,
+                    int fused, void* out_attn, void* out_q, void* out_k, void* out_v);
+
+/* The residual + RMSNorm step (Section 3.1's f_theta): h (device fp32 [M, d_model], in and out) += the
+ * n_part split-K partial sums `partials` (device fp32 [n_part, M, d_model], added in order; n_part may be
+ * 0), then out (cfg.dtype [M, d_model]) = h / sqrt(mean(h^2) + rms_eps) * gain (device fp32 [d_model]).
+ * Asynchronous.  Errors: SSD_EINVAL, SSD_ERANGE. */
+int ssd_k_norm(ssd_ctx* ctx, float* h, const float* partials, int n_part, const float* gain, int M, void* out);
 
 /* SSD_LIN_LM of ssd_k_linear for callers that cannot allocate device memory or hand over a region
  * for partial results of their own: code under HIP graph capture, tight serving loops, harnesses
@@ -52,30 +84,6 @@ int ssd_k_lm_head_static(ssd_ctx* ctx, const void* x, int M, void* out);
 int ssd_k_accept(ssd_ctx* ctx, int n, const int* seqs, const int32_t* block_tok, const uint64_t* masked,
                  const int* block_len, const int32_t* draft_pos, const int32_t* draft_tok, const int* n_draft,
                  int n_draft_next, const float* row_conf, const int32_t* row_argmax, const ssd_step_out* out);
-
-/* Streams `bytes` of device memory with the access pattern of the GEMM's weight stream
- * (work_groups x waves_per_wg waves, `depth` 16-byte loads in flight per lane: 4, 8 or 16):
- * the HBM read rate the chip sustains, i.e. the practical ceiling of the roofline.
- * `sink` is 16 bytes of device scratch.  Asynchronous on `hip_stream`. */
-int ssd_debug_stream_read(const void* src, size_t bytes, int work_groups, int waves_per_wg, int depth,
-                          void* sink, void* hip_stream);
-
-/* Measurement aid: while on (1), every forward of the context leaves out the gate/up GEMM launch of each
- * layer (the feed-forward block then reads stale activations: the results of such forwards are invalid, their
- * kernels and launch order otherwise unchanged).  The difference between the duration of a forward with and
- * without it, divided by the layer count, is what one gate/up launch costs inside the forward, measured with
- * two events per forward instead of two per kernel.  Returns the previous setting or an error. */
-int ssd_debug_skip_gate_up(ssd_ctx* ctx, int on);
-
-/* The loads of a weight-streaming GEMM and nothing else: each of `work_groups` work-groups (512
- * threads) reads all shared_bytes of `shared` (the activations every work-group needs) and its own
- * priv_bytes_per_wg of `priv` (work-group g reads [g, g+1) * priv_bytes_per_wg: its share of the
- * weights, non-temporal), evenly interleaved, with `threads` (512 or 1024) lanes and `depth` (4 or 8)
- * 16-byte loads in flight per lane.  Both sizes must be multiples of threads * depth * 16 bytes; `priv`
- * must hold work_groups * priv_bytes_per_wg bytes.  The duration is what the load path alone needs for
- * that GEMM's bytes.  `sink` is 16 bytes of device scratch.  Asynchronous on `hip_stream`. */
-int ssd_debug_mixed_read(const void* shared, size_t shared_bytes, const void* priv, size_t priv_bytes_per_wg,
-                         int work_groups, int threads, int depth, void* sink, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -14,6 +14,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssd_mi355x.so")
+MEASURE_LIB_PATH = os.path.join(_HERE, "libssd_measure.so")
 
 SSD_MAX_DRAFT = 15
 SSD_F32, SSD_BF16 = 0, 1
@@ -23,7 +24,8 @@ EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd
            "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept", "ssd_k_lm_head_static",
-           "ssd_debug_stream_read", "ssd_debug_mixed_read", "ssd_debug_skip_gate_up"]
+           "ssd_k_write_cache", "ssd_k_attention", "ssd_k_norm"]
+MEASURE_EXPORTS = ["ssd_measure_stream_read", "ssd_measure_mixed_read"]
 LIN_QKV, LIN_O, LIN_GU, LIN_DOWN, LIN_LM = range(5)
 
 
@@ -43,6 +45,10 @@ class SsdWeights(C.Structure):
 class SsdStepOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("n_accept", "acc_pos", "acc_tok", "n_next", "next_pos", "next_tok",
                                            "row_maxlogit", "row_argmax", "row_conf")]
+
+
+class SsdKNode(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("seq", "S", "blen", "T")]
 
 
 class SsdStats(C.Structure):
@@ -81,9 +87,8 @@ def load_library() -> C.CDLL:
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cross_block.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cache_mode.argtypes = [C.c_void_p, C.c_int, C.c_int]
-    lib.ssd_debug_skip_gate_up.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_acceptance_limit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
-                                         C.c_void_p, C.c_void_p, C.c_void_p]
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ssd_refresh_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
                                    C.POINTER(SsdStepOut)]
     for n in ("ssd_profile_begin", "ssd_profile_end"):
@@ -91,14 +96,26 @@ def load_library() -> C.CDLL:
     lib.ssd_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                      C.POINTER(C.c_double)]
     lib.ssd_k_linear.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+    lib.ssd_k_write_cache.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.ssd_k_attention.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(SsdKNode), C.c_void_p, C.c_int, C.c_int,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ssd_k_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
     lib.ssd_k_lm_head_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
-    lib.ssd_debug_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
-    lib.ssd_debug_mixed_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int,
-                                         C.c_void_p, C.c_void_p]
     lib.ssd_strerror.restype = C.c_char_p
     lib.ssd_strerror.argtypes = [C.c_int]
     lib.ssd_last_error.restype = C.c_char_p
     lib.ssd_last_error.argtypes = [C.c_void_p]
+    return lib
+
+
+def load_measure_library() -> C.CDLL:
+    """The measurement kernels (streaming-read ceiling, a GEMM's loads alone): a library of their own."""
+    if not os.path.exists(MEASURE_LIB_PATH):
+        raise ImportError(f"{MEASURE_LIB_PATH} is missing: build it with `python -m paper_2510_04147_amd.build`")
+    lib = C.CDLL(MEASURE_LIB_PATH)
+    lib.ssd_measure_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.ssd_measure_mixed_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int,
+                                           C.c_void_p, C.c_void_p]
     return lib
 
 
@@ -184,9 +201,6 @@ class SSD:
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = (self.workspace.data_ptr() + 255) & ~255
         self.stream = torch.cuda.current_stream(dev)
-        # ssd_create reads the weights on this stream (it repacks them): whatever produced
-        # them, on any stream, must have finished
-        torch.cuda.synchronize(dev)
         h = C.c_void_p()
         rc = self.lib.ssd_create(C.byref(self.ccfg), C.byref(w), C.c_void_p(base), C.c_size_t(nbytes),
                                  C.c_void_p(self.stream.cuda_stream), C.byref(h))
@@ -242,12 +256,12 @@ class SSD:
         toks = np.zeros(gen_len, dtype=np.int32)
         matched, forwards = np.zeros(k_max, dtype=np.int64), np.zeros(k_max, dtype=np.int64)
         rounds = np.zeros(1, dtype=np.int64)
+        reduction = np.zeros(k_max, dtype=np.float64)
         self._chk(self.lib.ssd_acceptance_limit(self.h, p.ctypes.data, len(p), gen_len, block, n_draft, k_max,
                                                 toks.ctypes.data, matched.ctypes.data, forwards.ctypes.data,
-                                                rounds.ctypes.data))
+                                                rounds.ctypes.data, reduction.ctypes.data))
         return toks, dict(steps=gen_len, rounds=int(rounds[0]), matched=[int(v) for v in matched],
-                          forwards=[int(v) for v in forwards],
-                          reduction=[1.0 - int(f) / gen_len for f in forwards])
+                          forwards=[int(v) for v in forwards], reduction=[float(v) for v in reduction])
 
     def set_graphs(self, on):
         return self._chk(self.lib.ssd_set_graphs(self.h, int(on)))
@@ -325,6 +339,27 @@ class SSD:
         """One linear step on caller-supplied rows x [M, K] (device tensor of the model dtype)."""
         assert x.is_contiguous() and out.is_contiguous() and x.device == self.device
         self._chk(self.lib.ssd_k_linear(self.h, which, layer, x.data_ptr(), x.shape[0], out.data_ptr()))
+
+    def k_write_cache(self, seq, layer, pos0, k, v):
+        """k, v: device tensors [n, Hkv, dh] of the model dtype (keys already rotated) into the cache."""
+        assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape and k.device == self.device
+        self._chk(self.lib.ssd_k_write_cache(self.h, seq, layer, pos0, k.shape[0], k.data_ptr(), v.data_ptr()))
+
+    def k_attention(self, layer, nodes, qkv, fused, out_attn, out_q=None, out_k=None, out_v=None):
+        """nodes: list of (seq, S, blen, T); qkv: device fp32 [n_part, M, (Hq+2Hkv)*dh]."""
+        arr = (SsdKNode * len(nodes))(*[SsdKNode(*nd) for nd in nodes])
+        assert qkv.dtype == torch.float32 and qkv.is_contiguous() and qkv.dim() == 3 and out_attn.is_contiguous()
+        ptr = lambda t: t.data_ptr() if t is not None else None
+        self._chk(self.lib.ssd_k_attention(self.h, layer, len(nodes), arr, qkv.data_ptr(), qkv.shape[0], int(fused),
+                                           out_attn.data_ptr(), ptr(out_q), ptr(out_k), ptr(out_v)))
+
+    def k_norm(self, h, partials, gain, out):
+        """h: device fp32 [M, d] (updated in place); partials: device fp32 [n_part, M, d] or None."""
+        assert h.dtype == torch.float32 and h.is_contiguous() and gain.dtype == torch.float32 and out.is_contiguous()
+        n_part = 0 if partials is None else partials.shape[0]
+        assert partials is None or (partials.dtype == torch.float32 and partials.is_contiguous())
+        self._chk(self.lib.ssd_k_norm(self.h, h.data_ptr(), partials.data_ptr() if n_part else None, n_part,
+                                      gain.data_ptr(), h.shape[0], out.data_ptr()))
 
     def k_lm_head_static(self, x, out):
         """The LM-head reduction of k_linear(LIN_LM, ...) with its partial results in the library's static array."""

@@ -8,7 +8,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssd_mi355x.so")
+MEASURE_LIB = os.path.join(HERE, "libssd_measure.so")      # measurement kernels only, not part of the product
 SOURCES = ["kernels_mfma.hip", "kernels_mfma_f32.hip", "ssd_api.hip", "kernels_plain.hip"]
+MEASURE_SOURCES = ["measure.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-result"]
@@ -25,14 +27,15 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    if verbose:
-        print("built", LIB)
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        objs = list(ex.map(_compile, SOURCES + MEASURE_SOURCES))
+    for lib, ob in ((LIB, objs[:len(SOURCES)]), (MEASURE_LIB, objs[len(SOURCES):])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *ob, "-o", lib]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+        if verbose:
+            print("built", lib)
     return LIB
 
 

@@ -430,46 +430,3 @@ bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, in
 #undef SSD_ATTN_ARGS
     return true;
 }
-
-// ------------------------------------------------------------------------
-// Measurement aid: a pure read of `bytes` with the access pattern of the
-// GEMM's weight stream (each wave walks its own contiguous region with
-// 16-byte loads, DEPTH independent loads in flight).  It gives the HBM read
-// rate the chip sustains for that pattern: the practical ceiling the GEMM is
-// measured against.
-// ------------------------------------------------------------------------
-template <int DEPTH>
-__global__ __launch_bounds__(512) void k_stream_read(const uint4* src, size_t n16_per_wave, unsigned* sink) {
-    const int lane = threadIdx.x & 63;
-    const size_t wave = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const uint4* p = src + wave * n16_per_wave + lane;
-    unsigned acc = 0;
-    for (size_t i = 0; i < n16_per_wave; i += 64 * DEPTH) {
-        uint4 v[DEPTH];
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) v[d] = p[i + (size_t)d * 64];
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
-    }
-    if (acc == 0x9e3779b9u) sink[0] = acc;      // practically never true; keeps the loads alive
-}
-
-extern "C" __attribute__((visibility("default"))) int ssd_debug_stream_read(const void* src, size_t bytes,
-                                                                            int work_groups, int waves_per_wg,
-                                                                            int depth, void* sink, void* stream) {
-    if (!src || !sink || work_groups < 1 || waves_per_wg < 1 || waves_per_wg > 8) return SSD_EINVAL;
-    const size_t waves = (size_t)work_groups * waves_per_wg;
-    size_t per = bytes / 16 / waves;
-    per -= per % (64 * 16);                      // whole unrolled steps for every depth
-    if (per == 0) return SSD_EINVAL;
-    hipStream_t st = (hipStream_t)stream;
-    if (depth == 16)
-        k_stream_read<16><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
-    else if (depth == 8)
-        k_stream_read<8><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
-    else if (depth == 4)
-        k_stream_read<4><<<work_groups, waves_per_wg * 64, 0, st>>>((const uint4*)src, per, (unsigned*)sink);
-    else
-        return SSD_EINVAL;
-    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
-}

@@ -824,58 +824,59 @@ void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out,
                                                                 (size_t)c->dm.max_rows * c->part_cols, out, n);
 }
 
+// Kernel-level entry points: caller-supplied keys and values (row-major [n, Hkv, dh], keys after the
+// rotary embedding) into a sequence's cache slot at positions [pos0, pos0 + n), fragment order.
+template <typename T>
+__global__ void k_write_cache(const T* __restrict__ k, const T* __restrict__ v, T* __restrict__ kcache,
+                              T* __restrict__ vcache, int Hkv, int dh, int pos0, size_t slot_base, int seq_stride) {
+    const int r = blockIdx.x, kvh = blockIdx.y;
+    const size_t hb = slot_base + (size_t)kvh * seq_stride * dh;
+    for (int ch = threadIdx.x; ch < dh; ch += blockDim.x) {
+        const size_t src = ((size_t)r * Hkv + kvh) * dh + ch;
+        kcache[hb + kfrag_off(pos0 + r, ch, dh)] = k[src];
+        vcache[hb + vfrag_off(pos0 + r, ch, dh)] = v[src];
+    }
+}
+
+void launch_write_cache(const ssd_ctx* c, int seq, int layer, int pos0, int n, const void* k, const void* v, hipStream_t st) {
+    const Dims& d = c->dm;
+    const size_t slot = (((size_t)layer * d.max_seqs + seq) * d.Hkv) * (size_t)d.seq_stride() * d.dh;
+    dim3 grid(n, d.Hkv);
+    if (d.dtype == SSD_F32)
+        k_write_cache<float><<<grid, 128, 0, st>>>((const float*)k, (const float*)v, (float*)c->b.kcache, (float*)c->b.vcache,
+                                                   d.Hkv, d.dh, pos0, slot, d.seq_stride());
+    else
+        k_write_cache<bf16_t><<<grid, 128, 0, st>>>((const bf16_t*)k, (const bf16_t*)v, (bf16_t*)c->b.kcache,
+                                                    (bf16_t*)c->b.vcache, d.Hkv, d.dh, pos0, slot, d.seq_stride());
+}
+
+// The nodes' own keys and values of a forward, from fragment order back to row-major [M, Hkv, dh].
+template <typename T>
+__global__ void k_read_own_kv(const FwdHeader* __restrict__ fw, const int* __restrict__ row_node,
+                              const T* __restrict__ kown, const T* __restrict__ vown, T* __restrict__ k,
+                              T* __restrict__ v, int Hkv, int dh, int vt_rows) {
+    const int row = blockIdx.x, kvh = blockIdx.y;
+    const NodeDesc nd = fw->nodes[row_node[row]];
+    const int prow = nd.vrow0 + (row - nd.row0);
+    const size_t hb = (size_t)kvh * vt_rows * dh;
+    for (int ch = threadIdx.x; ch < dh; ch += blockDim.x) {
+        const size_t dst = ((size_t)row * Hkv + kvh) * dh + ch;
+        k[dst] = kown[hb + kfrag_off(prow, ch, dh)];
+        v[dst] = vown[hb + vfrag_off(prow, ch, dh)];
+    }
+}
+
+void launch_read_own_kv(const ssd_ctx* c, int M, void* k, void* v, hipStream_t st) {
+    const Dims& d = c->dm;
+    dim3 grid(M, d.Hkv);
+    if (d.dtype == SSD_F32)
+        k_read_own_kv<float><<<grid, 128, 0, st>>>(c->b.fwd, c->b.row_node, (const float*)c->b.kown, (const float*)c->b.vown,
+                                                   (float*)k, (float*)v, d.Hkv, d.dh, d.vt_rows());
+    else
+        k_read_own_kv<bf16_t><<<grid, 128, 0, st>>>(c->b.fwd, c->b.row_node, (const bf16_t*)c->b.kown,
+                                                    (const bf16_t*)c->b.vown, (bf16_t*)k, (bf16_t*)v, d.Hkv, d.dh, d.vt_rows());
+}
+
 void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st) {
     k_int_to_float<<<(n + 255) / 256, 256, 0, st>>>(src, dst, n);
-}
-
-// ------------------------------------------------------------------------
-// Measurement aid: the loads of a weight-streaming GEMM and nothing else.  Every work-group reads
-// the SAME `shared` buffer once (the activations, served by L2) and its OWN slice of `priv` (its share
-// of the weights, from HBM, non-temporal like the GEMM's), interleaved evenly, 4 x 16 bytes in
-// flight per lane (DEPTH 4; or 8, and 512 or 1024 lanes).  Its duration is what the load path alone needs
-// for a GEMM's bytes in a one-tile-per-CU decomposition: the floor of such a kernel whatever its arithmetic costs.
-// ------------------------------------------------------------------------
-typedef unsigned int mr_u32x4 __attribute__((ext_vector_type(4)));
-template <int DEPTH, int THREADS>
-__global__ __launch_bounds__(THREADS) void k_mixed_read(const mr_u32x4* __restrict__ shared, int steps_s,
-                                                        const mr_u32x4* __restrict__ priv, int steps_p, unsigned* sink) {
-    const int tid = threadIdx.x;
-    const mr_u32x4* pp = priv + (size_t)blockIdx.x * steps_p * DEPTH * THREADS;
-    unsigned acc = 0;
-    int ip = 0;
-    for (int is = 0; is < steps_s; ++is) {
-        mr_u32x4 v[DEPTH], w[DEPTH];
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) v[d] = shared[((size_t)is * DEPTH + d) * THREADS + tid];
-        // private steps spread evenly over the shared ones: those whose index falls into this interval
-        const int hi = (int)(((long long)(is + 1) * steps_p) / steps_s);
-        for (; ip < hi; ++ip) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) w[d] = __builtin_nontemporal_load(&pp[((size_t)ip * DEPTH + d) * THREADS + tid]);
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) acc ^= w[d].x ^ w[d].y ^ w[d].z ^ w[d].w;
-        }
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) acc ^= v[d].x ^ v[d].y ^ v[d].z ^ v[d].w;
-    }
-    if (acc == 0x9e3779b9u) sink[0] = acc;      // practically never true; keeps the loads alive
-}
-
-extern "C" __attribute__((visibility("default"))) int ssd_debug_mixed_read(const void* shared, size_t shared_bytes,
-                                                                           const void* priv, size_t priv_bytes_per_wg,
-                                                                           int work_groups, int threads, int depth,
-                                                                           void* sink, void* stream) {
-    if ((threads != 512 && threads != 1024) || (depth != 4 && depth != 8)) return SSD_EINVAL;
-    const size_t step = (size_t)threads * depth * 16;            // bytes one work-group reads per step
-    if (!shared || !priv || !sink || work_groups < 1 || shared_bytes < step || shared_bytes % step ||
-        priv_bytes_per_wg % step || shared_bytes / step > (1u << 20) || priv_bytes_per_wg / step > (1u << 20))
-        return SSD_EINVAL;
-    const int ss = (int)(shared_bytes / step), sp = (int)(priv_bytes_per_wg / step);
-    hipStream_t st = (hipStream_t)stream;
-    const mr_u32x4 *a = (const mr_u32x4*)shared, *b = (const mr_u32x4*)priv;
-    if (threads == 512 && depth == 4) k_mixed_read<4, 512><<<work_groups, 512, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
-    else if (threads == 512) k_mixed_read<8, 512><<<work_groups, 512, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
-    else if (depth == 4) k_mixed_read<4, 1024><<<work_groups, 1024, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
-    else k_mixed_read<8, 1024><<<work_groups, 1024, 0, st>>>(a, ss, b, sp, (unsigned*)sink);
-    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_EHIP;
 }

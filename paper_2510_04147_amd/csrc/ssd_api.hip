@@ -182,6 +182,12 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
             g_create_err = "null per-layer weight pointer";
             return SSD_EINVAL;
         }
+    // The repack kernels below read the weights on `hip_stream`; whatever wrote them, on any stream
+    // of this device, has to be complete first.  Creation is a one-time set-up call: wait for the device.
+    {
+        hipError_t es = hipDeviceSynchronize();
+        if (es != hipSuccess) { g_create_err = std::string("hipDeviceSynchronize: ") + hipGetErrorString(es); return SSD_EHIP; }
+    }
     ssd_ctx* c = new (std::nothrow) ssd_ctx();
     if (!c) { g_create_err = "host allocation failed"; return SSD_ENOMEM; }
     c->dm = d;
@@ -224,7 +230,6 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->tree_mode = 0;
     c->cross_block = 0;
     c->cache_mode = 0;
-    c->debug_skip_gate_up = 0;
     c->refresh_interval = 0;
     memset(c->total_len, 0, sizeof c->total_len);
     c->use_graphs = 0;
@@ -330,13 +335,6 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_cache_mode(ssd_ctx
     return old;
 }
 
-extern "C" __attribute__((visibility("default"))) int ssd_debug_skip_gate_up(ssd_ctx* c, int on) {
-    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
-    const int old = c->debug_skip_gate_up;
-    c->debug_skip_gate_up = on;
-    return old;
-}
-
 extern "C" __attribute__((visibility("default"))) int ssd_set_tree_mode(ssd_ctx* c, int mode) {
     if (!c || (mode != 0 && mode != 1)) return SSD_EINVAL;
     const int old = c->tree_mode;
@@ -432,7 +430,6 @@ struct Upload {           // block state to push before the forward (stateless A
 static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void* out, int M, int* n_split) {
     ProfScope ps(c, cls);
     *n_split = 1;
-    if (cls == KC_GEMM_GU && c->debug_skip_gate_up) return;       // measurement aid, see ssd_debug_skip_gate_up
     if (c->kernel_path >= 1 && c->dm.dtype == SSD_BF16 && launch_gemm_mfma(c, epi, X, W, out, M, n_split, c->stream))
         return;
     const int N = epi == EPI_SWIGLU ? W.N / 2 : W.N;
@@ -440,10 +437,10 @@ static void gemm(ssd_ctx* c, int cls, int epi, const void* X, const Wt& W, void*
     launch_gemm_plain(c, epi, X, W.raw, out, M, N, W.K, c->stream);
 }
 
-// Runs one forward over the groups in `hd` (decode groups first).  raw / n_raw:
-// tokens of GM_RAW groups; ups: block states to upload first.
-static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int n_raw, const Upload* ups, int n_ups,
-                       const ssd_step_out* out, const float* k_conf = nullptr, const int32_t* k_arg = nullptr) {
+// Copies a forward's descriptor, its raw tokens and the block states to upload to the device through
+// the pinned staging ring (asynchronous on the context's stream).
+static int stage_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int n_raw, const Upload* ups, int n_ups,
+                         const ssd_step_out* out) {
     const Dims& d = c->dm;
     hipStream_t st = c->stream;
     // ---- stage and upload the descriptor
@@ -469,6 +466,19 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
     HIPCHK(c, hipEventRecord(c->stage_ev[slot], st));
     c->stage_used[slot] = true;
 
+    return SSD_OK;
+}
+
+// Runs one forward over the groups in `hd` (decode groups first).  raw / n_raw:
+// tokens of GM_RAW groups; ups: block states to upload first.
+static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int n_raw, const Upload* ups, int n_ups,
+                       const ssd_step_out* out, const float* k_conf = nullptr, const int32_t* k_arg = nullptr) {
+    hipStream_t st = c->stream;
+    {
+        const int rc = stage_forward(c, hd, raw, n_raw, ups, n_ups, out);
+        if (rc != SSD_OK) return rc;
+    }
+    const Dims& d = c->dm;
     const int M = hd.M, ML = hd.M_logits;
     if (k_conf) {
         // kernel-level entry: the caller supplies every row's confidence and arg-max; only the
@@ -750,6 +760,19 @@ extern "C" __attribute__((visibility("default"))) int ssd_refresh_kv(ssd_ctx* c,
     return rc;
 }
 
+// The two timing events of a decoding loop, destroyed on every way out of it.
+struct EventPair {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t create() {
+        hipError_t e = hipEventCreate(&a);
+        return e != hipSuccess ? e : hipEventCreate(&b);
+    }
+    ~EventPair() {
+        if (a) (void)hipEventDestroy(a);
+        if (b) (void)hipEventDestroy(b);
+    }
+};
+
 // ssd_generate with the dual cache: a forward over the whole sequence renews the cache at the start
 // and whenever refresh_interval tokens have been decoded since (0: the block length), and is itself the
 // decoding step of that moment; a chain carries no more drafts than fit before the next refresh, so
@@ -768,10 +791,10 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
     const auto t_begin = std::chrono::steady_clock::now();
     ssd_stats sta;
     memset(&sta, 0, sizeof sta);
-    hipEvent_t ev0, ev1;
-    HIPCHK(c, hipEventCreate(&ev0));
-    HIPCHK(c, hipEventCreate(&ev1));
-    auto done = [&](int rc) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return rc; };
+    EventPair evp;
+    HIPCHK(c, evp.create());
+    const hipEvent_t ev0 = evp.a, ev1 = evp.b;
+    auto done = [&](int rc) { return rc; };
     const int n_blocks = (gen_len + block - 1) / block;
     std::vector<std::vector<int32_t>> x(n);
     int blk[SSD_MAX_SEQS], n_masked[SSD_MAX_SEQS], n_dr[SSD_MAX_SEQS], since[SSD_MAX_SEQS];
@@ -871,10 +894,10 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
     const auto t_begin = std::chrono::steady_clock::now();
     ssd_stats sta;
     memset(&sta, 0, sizeof sta);
-    hipEvent_t ev0, ev1;
-    HIPCHK(c, hipEventCreate(&ev0));
-    HIPCHK(c, hipEventCreate(&ev1));
-    auto done = [&](int rc) { (void)hipEventDestroy(ev0); (void)hipEventDestroy(ev1); return rc; };
+    EventPair evp;
+    HIPCHK(c, evp.create());
+    const hipEvent_t ev0 = evp.a, ev1 = evp.b;
+    auto done = [&](int rc) { return rc; };
     int rc;
     // prompt prefill, one segment per forward
     for (int i = 0; i < n; ++i) {
@@ -1023,7 +1046,8 @@ extern "C" __attribute__((visibility("default"))) int ssd_generate(ssd_ctx* c, i
 // ------------------------------------------- acceptance-rate limit (Section 5.1, Table 2)
 extern "C" __attribute__((visibility("default"))) int ssd_acceptance_limit(ssd_ctx* c, const int32_t* prompt, int prompt_len, int gen_len,
                                                                            int block, int n_draft, int k_max, int32_t* out_tokens,
-                                                                           int64_t* matched, int64_t* forwards, int64_t* rounds) {
+                                                                           int64_t* matched, int64_t* forwards, int64_t* rounds,
+                                                                           double* reduction) {
     if (!c) return SSD_EINVAL;
     const Dims& d = c->dm;
     if (!prompt || prompt_len < 1 || gen_len < 1 || !matched || !forwards || k_max < 1) { set_err(c, "acceptance_limit: bad argument"); return SSD_EINVAL; }
@@ -1083,6 +1107,9 @@ extern "C" __attribute__((visibility("default"))) int ssd_acceptance_limit(ssd_c
         if (b + 1 < n_blocks && (rc = ssd_prefill_kv(c, 0, blk_tok.data(), bl, S)) != SSD_OK) return rc;
     }
     if (rounds) *rounds = n_rounds;
+    // Table 2's quantity: the share of stepwise forwards an ideal verification tree would save
+    if (reduction)
+        for (int k = 0; k < k_max; ++k) reduction[k] = 1.0 - (double)forwards[k] / (double)gen_len;
     return SSD_OK;
 }
 
@@ -1097,6 +1124,89 @@ extern "C" __attribute__((visibility("default"))) int ssd_k_accept(ssd_ctx* c, i
     if (!n_draft || !row_conf || !row_argmax) { set_err(c, "ssd_k_accept: null argument"); return SSD_EINVAL; }
     return step_common(c, "ssd_k_accept", n, seqs, block_tok, masked, nullptr, block_len, draft_pos, draft_tok, n_draft,
                        n_draft_next, out, row_conf, row_argmax);
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_k_write_cache(ssd_ctx* c, int seq, int layer, int pos0, int n,
+                                                                        const void* k, const void* v) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!k || !v || n < 1 || pos0 < 0) { set_err(c, "k_write_cache: null pointer, n < 1 or pos0 < 0"); return SSD_EINVAL; }
+    if (seq < 0 || seq >= d.max_seqs || layer < 0 || layer >= d.L) { set_err(c, "k_write_cache: seq or layer out of range"); return SSD_ERANGE; }
+    if ((long long)pos0 + n > d.max_seq_len) { set_err(c, "k_write_cache: positions exceed max_seq_len"); return SSD_ERANGE; }
+    launch_write_cache(c, seq, layer, pos0, n, k, v, c->stream);
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_k_attention(ssd_ctx* c, int layer, int n_nodes, const ssd_k_node* nodes,
+                                                                      const float* qkv, int n_part, int fused, void* out_attn,
+                                                                      void* out_q, void* out_k, void* out_v) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!nodes || !qkv || !out_attn || n_nodes < 1 || n_part < 1) { set_err(c, "k_attention: null pointer, no node or no partial sum"); return SSD_EINVAL; }
+    if (layer < 0 || layer >= d.L || n_nodes > d.max_nodes() || n_nodes > SSD_MAX_GROUPS || n_part > SSD_MAX_SPLIT) {
+        set_err(c, "k_attention: layer, node count or partial-sum count out of range");
+        return SSD_ERANGE;
+    }
+    FwdHeader hd;
+    memset(&hd, 0, sizeof hd);
+    int max_blen = 0;
+    bool any_suffix = false;
+    for (int i = 0; i < n_nodes; ++i) {
+        const ssd_k_node& nd = nodes[i];
+        if (nd.seq < 0 || nd.seq >= d.max_seqs || nd.blen < 1 || nd.S < 0 || (long long)nd.S + nd.blen > d.max_seq_len ||
+            (nd.T != 0 && (nd.T < nd.S + nd.blen || nd.T > d.max_seq_len)) || hd.M + nd.blen > d.max_rows) {
+            set_err(c, "k_attention: node %d does not fit the context (seq %d, S %d, blen %d, T %d)", i, nd.seq, nd.S, nd.blen, nd.T);
+            return SSD_ERANGE;
+        }
+        add_group(hd, nd.seq, GM_RAW, nd.blen, nd.S, 1, 0, 0, 0, hd.M, -1, 0, false, nd.T);
+        hd.nodes[hd.n_nodes - 1].write_kv = 0;           // the cache is the caller's: nothing is appended
+        max_blen = std::max(max_blen, nd.blen);
+        any_suffix |= nd.T > nd.S + nd.blen;
+    }
+    const int M = hd.M;
+    const bool mfma = c->kernel_path >= 1 && d.dtype == SSD_BF16;
+    if (fused && !(mfma && c->kernel_path == 1 && attn_mfma_can_fuse_rope(c, max_blen))) {
+        set_err(c, "k_attention: the fused rotary stage needs bf16, kernel path 1, head size 128 and nodes of at most 32 rows");
+        return SSD_EINVAL;
+    }
+    if (fused && (out_q || out_k || out_v)) { set_err(c, "k_attention: the fused kernel keeps q, k and v on chip"); return SSD_EINVAL; }
+    std::vector<int32_t> zeros((size_t)M, 0);
+    int rc = stage_forward(c, hd, zeros.data(), M, nullptr, 0, nullptr);
+    if (rc != SSD_OK) return rc;
+    hipStream_t st = c->stream;
+    const size_t stride = (size_t)d.max_rows * c->part_cols;
+    for (int sp = 0; sp < n_part; ++sp)
+        HIPCHK(c, hipMemcpyAsync(c->b.part + sp * stride, qkv + (size_t)sp * M * d.nqkv(), (size_t)M * d.nqkv() * 4,
+                                 hipMemcpyDeviceToDevice, st));
+    launch_build_rows(c, st, hd.n_nodes);
+    if (!fused) launch_rope(c, hd.n_nodes, max_blen, layer, n_part, st);
+    if (!(mfma && launch_attn_mfma(c, hd.n_nodes, max_blen, layer, fused ? n_part : -1, any_suffix, st)))
+        launch_attn_plain(c, M, layer, st);
+    HIPCHK(c, hipMemcpyAsync(out_attn, c->b.attn, (size_t)M * d.nq() * d.esz(), hipMemcpyDeviceToDevice, st));
+    if (out_q) HIPCHK(c, hipMemcpyAsync(out_q, c->b.q, (size_t)M * d.nq() * d.esz(), hipMemcpyDeviceToDevice, st));
+    if (out_k && out_v) launch_read_own_kv(c, M, out_k, out_v, st);
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_k_norm(ssd_ctx* c, float* h, const float* partials, int n_part,
+                                                                 const float* gain, int M, void* out) {
+    if (!c) return SSD_EINVAL;
+    const Dims& d = c->dm;
+    if (!h || !gain || !out || M < 1 || n_part < 0 || (n_part > 0 && !partials)) { set_err(c, "k_norm: null pointer, M < 1 or n_part < 0"); return SSD_EINVAL; }
+    if (M > d.max_rows || n_part > SSD_MAX_SPLIT) { set_err(c, "k_norm: M or n_part out of range"); return SSD_ERANGE; }
+    hipStream_t st = c->stream;
+    const size_t stride = (size_t)d.max_rows * c->part_cols;
+    HIPCHK(c, hipMemcpyAsync(c->b.h, h, (size_t)M * d.d * 4, hipMemcpyDeviceToDevice, st));
+    for (int sp = 0; sp < n_part; ++sp)
+        HIPCHK(c, hipMemcpyAsync(c->b.part + sp * stride, partials + (size_t)sp * M * d.d, (size_t)M * d.d * 4,
+                                 hipMemcpyDeviceToDevice, st));
+    launch_norm(c, M, gain, n_part, st);
+    HIPCHK(c, hipMemcpyAsync(h, c->b.h, (size_t)M * d.d * 4, hipMemcpyDeviceToDevice, st));
+    HIPCHK(c, hipMemcpyAsync(out, c->b.xn, (size_t)M * d.d * d.esz(), hipMemcpyDeviceToDevice, st));
+    HIPCHK(c, hipGetLastError());
+    return SSD_OK;
 }
 
 extern "C" __attribute__((visibility("default"))) int ssd_k_lm_head_static(ssd_ctx* c, const void* x, int M,

@@ -198,7 +198,6 @@ struct ssd_ctx {
     // Cache of the paper's experiments (Section 4.1), 0 = exact block-causal prefix cache: 1 = dual
     // cache, keys and values of ALL positions renewed by a full forward every refresh_interval
     // decoded tokens (0 = once per block).  total_len[seq] > 0: positions up to there are cached.
-    int debug_skip_gate_up;  // measurement aid: forwards leave out the gate/up GEMM (their results are invalid)
     int cache_mode, refresh_interval;
     int total_len[SSD_MAX_SEQS];
     int cached_len[SSD_MAX_SEQS];
@@ -238,6 +237,9 @@ int lm_tiles_plain(int V);
 // out[M,N] = sum over the first n_part split-K partial buffers, in split order
 void launch_sum_partials(const ssd_ctx* c, int M, int N, int n_part, float* out, hipStream_t st);
 void launch_int_to_float(const int* src, float* dst, int n, hipStream_t st);
+// kernel-level entry points: caller-supplied keys / values into the cache; a forward's own keys / values back out
+void launch_write_cache(const ssd_ctx* c, int seq, int layer, int pos0, int n, const void* k, const void* v, hipStream_t st);
+void launch_read_own_kv(const ssd_ctx* c, int M, void* k, void* v, hipStream_t st);
 // rank[i] = number of tokens ahead of tok[i] in row pos[i] of logits [*, V]: higher logit, or equal and
 // lower id; the mask token never counts
 struct RankPairs { int n; int pos[SSD_MAX_DRAFT + 1]; int tok[SSD_MAX_DRAFT + 1]; };

@@ -9,9 +9,9 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
+def declared_symbols(headers=("ssd.h", "ssd_kernels.h")):
     syms = set()
-    for h in ("ssd.h", "ssd_kernels.h"):
+    for h in headers:
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         syms |= set(re.findall(r"\b(ssd_[a-z_]+)\s*\(", text))
@@ -34,6 +34,19 @@ def test_every_declared_symbol_is_exported(lib):
     for s in syms:
         assert hasattr(lib, s), f"{s} declared in include/ssd.h but not exported"
     assert sorted(binding.EXPORTS) == syms
+
+
+def test_measurement_kernels_live_in_their_own_library(lib):
+    """The product library exports no measurement aid; the measurement library exports what its header declares."""
+    from paper_2510_04147_amd import binding
+    mlib = binding.load_measure_library()
+    syms = declared_symbols(("ssd_measure.h",))
+    assert syms == sorted(binding.MEASURE_EXPORTS)
+    for s in syms:
+        assert hasattr(mlib, s)
+        assert not hasattr(lib, s)
+    for s in ("ssd_debug_skip_gate_up", "ssd_debug_stream_read", "ssd_debug_mixed_read"):
+        assert not hasattr(lib, s)
 
 
 def test_struct_layouts_match_header():
@@ -73,4 +86,4 @@ def test_config_validation_needs_no_gpu(lib):
         assert getattr(lib, name)(None, 1) == -1, name
     assert lib.ssd_set_cache_mode(None, 1, 8) == -1
     assert lib.ssd_refresh_kv(None, 0, None, 0, 0, 0, 0, None) == -1
-    assert lib.ssd_acceptance_limit(None, None, 0, 0, 0, 0, 0, None, None, None, None) == -1
+    assert lib.ssd_acceptance_limit(None, None, 0, 0, 0, 0, 0, None, None, None, None, None) == -1

@@ -32,7 +32,7 @@ def test_cfg3_block64_depth8(w8b):
     sigma = parity_util.operand_noise_floor(cfg, w, prompt, 64, torch.float32)
     tol = parity_util.bf16_tolerances(sigma)
     _, _, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 64, 64, 8, torch.float32, max_forwards=4,
-                                           verbose=False, **tol)
+                                           verbose=False, literal=True, sigma=sigma, **tol)
     print("cfg3 totals", tot, "sigma", sigma)
     assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
     eng.close()
@@ -48,6 +48,14 @@ def test_cfg4_batch4_long_prefix(w8b):
     for i in (0, 3):
         solo, _ = eng.generate([prompts[i]], 64, 32, 0)
         assert np.array_equal(both[i], solo[0]), f"sequence {i} of the batch differs from its solo stepwise run"
+    # the batch against the oracle: the first forwards of every sequence (the block-start draft, then 5-node
+    # verification forwards), all four sequences in ONE forward each, each sequence compared with its own oracle run
+    sigma = parity_util.operand_noise_floor(cfg, w, prompts[0], 32, torch.float32)
+    tol = parity_util.bf16_tolerances(sigma)
+    tot = parity_util.teacher_forced_batch(eng, cfg, w, prompts, 32, 32, 4, torch.float32, max_forwards=3, sigma=sigma, **tol)
+    print("cfg4 totals", tot, "sigma", sigma)
+    assert tot["forwards"] == 3 and tot["rows"] >= 4 * 3 * 28
+    assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
     eng.close()
 
 
@@ -76,7 +84,7 @@ def test_cfg5_gqa_batch8_depth8():
     sigma = parity_util.operand_noise_floor(cfg, w, prompts[0], 32, torch.float32)
     tol = parity_util.bf16_tolerances(sigma)
     _, _, tot = parity_util.teacher_forced(eng, cfg, w, prompts[0], 32, 32, 8, torch.float32, max_forwards=3,
-                                           verbose=False, **tol)
+                                           verbose=False, literal=True, sigma=sigma, **tol)
     print("cfg5 totals", tot, "sigma", sigma)
     assert tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
     eng.close()

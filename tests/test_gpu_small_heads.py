@@ -26,7 +26,8 @@ def test_head_size_64_gqa_bf16():
         tol = parity_util.bf16_tolerances(sigma)
         for path in (1, 0):                                  # MFMA kernels, then the plain kernels on the same model
             eng.set_kernel_path(path)
-            ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 64, 32, 4, torch.float32, verbose=False, **tol)
+            ref, st, tot = parity_util.teacher_forced(eng, cfg, w, prompt, 64, 32, 4, torch.float32, verbose=False,
+                                                      literal=path == 1, sigma=sigma, **tol)
             print(f"path {path}: sigma {sigma:.4f}", tot)
             assert tot["forwards"] == st["forwards"] and tot["rms_dlogit"] <= 1.5 * sigma + 2e-3
             assert tot["tok_exempt"] <= 0.10 * tot["rows"]

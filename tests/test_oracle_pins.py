@@ -579,3 +579,91 @@ def test_acceptance_limit_probe_invariants_and_upper_bound(tiny, N):
     w["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w0["layers"]]
     _, pz = decode.acceptance_limit_probe(w, cfg, prompt, gen_len, block, N, 3)
     assert pz["matched"] == [gen_len] * 3 and abs(pz["reduction"][0] - N / (N + 1)) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# cfg["operand_dtype"]: where the oracle rounds matrix-product operands.  The bf16 GPU tolerances are
+# multiples of the noise this rounding causes, so its placement is pinned: every operand of every
+# matrix product is representable in the operand type, nothing else changes, and the resulting noise
+# floor equals a stored value.
+# --------------------------------------------------------------------------
+class _MatmulSpy:
+    """Records both operands of every `a @ b` evaluated while active."""
+
+    def __enter__(self):
+        self.calls = []
+        self._orig = torch.Tensor.__matmul__
+        spy = self
+
+        def patched(a, b):
+            spy.calls.append((a.detach().clone(), b.detach().clone()))
+            return spy._orig(a, b)
+
+        torch.Tensor.__matmul__ = patched
+        return self
+
+    def __exit__(self, *exc):
+        torch.Tensor.__matmul__ = self._orig
+
+
+def _representable(x, dt):
+    return bool((x.to(dt).to(x.dtype) == x).all())
+
+
+def test_operand_dtype_rounds_every_matmul_operand_and_nothing_else():
+    cfg = synth.model_config("tiny", dtype="bf16", n_layers=2, d_model=128, n_q_heads=4, n_kv_heads=2, head_dim=32,
+                             d_ffn=256, vocab=96)
+    w = synth.gen_weights(cfg, 41, std=0.08)
+    prompt = synth.gen_prompt(cfg, 42, 12)
+    block = [cfg["mask_id"]] * 8
+
+    def run(c):
+        cache = model.KVCache(c["n_layers"])
+        _, kv = model.forward_segment(w, c, prompt, 0, cache, torch.float64, need_logits=False)
+        cache.append(kv)
+        with _MatmulSpy() as spy:
+            logits, _ = model.forward_segment(w, c, block, len(prompt), cache, torch.float64)
+        return logits, spy.calls
+
+    exact, calls_exact = run(dict(cfg))                               # key absent
+    none, calls_none = run(dict(cfg, operand_dtype=None))
+    rounded, calls_bf16 = run(dict(cfg, operand_dtype=torch.bfloat16))
+    # per layer: QKV, (scores, weighted values) per query head, output, gate/up, down; then the LM head
+    per_layer = 1 + 2 * cfg["n_q_heads"] + 1 + 1 + 1
+    assert len(calls_exact) == len(calls_none) == len(calls_bf16) == cfg["n_layers"] * per_layer + 1
+    assert torch.equal(exact, none), "operand_dtype=None must leave the evaluation untouched"
+    for (a0, b0), (a1, b1) in zip(calls_exact, calls_none):
+        assert torch.equal(a0, a1) and torch.equal(b0, b1)
+    # rounded mode: both operands of every product are exactly representable in bf16 ...
+    for i, (a, b) in enumerate(calls_bf16):
+        assert _representable(a, torch.bfloat16) and _representable(b, torch.bfloat16), f"matmul {i} has an unrounded operand"
+    # ... whereas in exact mode every activation operand is not (the check has teeth), and the weights are
+    act_unrounded = sum(not _representable(a, torch.bfloat16) for a, _ in calls_exact)
+    assert act_unrounded == len(calls_exact)
+    # the rounding is a perturbation, not another function: logits move by a small fraction of their spread
+    dev = (rounded - exact).abs().max().item()
+    assert 0 < dev < 0.05 * exact.std().item()
+    # the residual stream, the norms' statistics and the softmax stay in the compute type: with an operand type that
+    # holds every fp64 value the rounded mode is the exact mode
+    same, _ = run(dict(cfg, operand_dtype=torch.float64))
+    assert torch.equal(same, exact)
+
+
+def test_operand_noise_floor_equals_the_stored_value():
+    """sigma of the small bf16 model, recomputed, against tests/golden/operand_sigma.txt (written by
+    tests/golden/make_operand_sigma.py from the oracle alone)."""
+    import importlib.util
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_operand_sigma", os.path.join(here, "golden", "make_operand_sigma.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = [float(l) for l in open(os.path.join(here, "golden", "operand_sigma.txt")) if not l.startswith("#")]
+    assert len(stored) == 1
+    assert mod.sigma() == pytest.approx(stored[0], rel=1e-6)
+    # dropping one rounding point (here: the softmax weights) must move sigma by far more than that tolerance
+    orig = model.attention
+    try:
+        model.attention = lambda q, k, v, allowed=None, cfg=None: orig(q, k, v, allowed, None)
+        assert abs(mod.sigma() - stored[0]) > 1e-3 * stored[0]
+    finally:
+        model.attention = orig

@@ -62,7 +62,8 @@ __device__ __forceinline__ uint16_t f2bf_m(float f) {
 template <int WN, int WK, int R, int MT, int EPI, int NCH, int DBG = 0, int DW = 4, int PX = 4, int KSTEPS = 2>
 __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, const uint4* Wp, void* outv, int M, int N,
                                                            int K, int ldx, int k_len, size_t split_stride,
-                                                           int mask_id, int n_tiles_out) {
+                                                           int mask_id, int n_tiles_out, int n_blocks, int n_split,
+                                                           int m_chunks_total) {
     constexpr int T = WN * WK * 64, KW = 16 * KSTEPS, KC = WK * KW, ROWS = MT * 32, LDW = KC + 8;
     constexpr int NST = 3;                              // LDS stages
     static_assert(DW >= 2 && DW <= 6 && PX >= 3 && PX <= 4, "ring depths");
@@ -75,15 +76,27 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wn = wave % WN, wk = wave / WN;
     const int lm = lane & 31, lh = lane >> 5;
-    // Work-groups go to the 8 XCDs round-robin by their linear id.  With split-K the low bits of
-    // blockIdx.x pick the k-slice, so the work-groups of one XCD read the same slice of the
-    // activations and find it in that XCD's L2; the n-block takes the remaining bits.
-    int bx = blockIdx.x, bz = blockIdx.z;
-    if (gridDim.z > 1 && gridDim.x % gridDim.z == 0) {
-        bz = blockIdx.x % gridDim.z;
-        bx = blockIdx.x / gridDim.z + (gridDim.x / gridDim.z) * blockIdx.z;
+    // The grid is one-dimensional; work-groups go to the 8 XCDs round-robin by their linear id, and every
+    // XCD has an L2 of its own.  The id is decoded so that with split-K all work-groups of an XCD take the
+    // same k-slice, i.e. read the same slice of the activations and find it in that XCD's L2, and so that
+    // the row chunks of one n-block (forwards with more rows than one pass holds) are neighbours on one
+    // XCD and stream the same weights at the same time.  A tile's result does not depend on where it runs.
+    int bx, bz, by;
+    {
+        const int split = n_split, mch = m_chunks_total;
+        const int id = blockIdx.x;
+        if (split <= 8 && 8 % split == 0 && n_blocks % (8 / split) == 0) {
+            const int xcd = id & 7, t = id >> 3, per = 8 / split;
+            bz = xcd % split;
+            by = t % mch;
+            bx = (t / mch) * per + xcd / split;
+        } else {
+            bz = id % split;
+            by = (id / split) % mch;
+            bx = id / (split * mch);
+        }
     }
-    const int m0 = blockIdx.y * ROWS;
+    const int m0 = by * ROWS;
     const int kbeg = bz * k_len, nchunks = NCH > 0 ? NCH : k_len / KC;
     const int KS = K >> 4, NT = N >> 5;
 
@@ -432,6 +445,7 @@ __global__ __launch_bounds__(WN* WK * 64) void k_gemm_mfma(const bf16_t* X, cons
 // ------------------------------------------------------------------------
 // launcher
 // ------------------------------------------------------------------------
+
 template <int WN, int WK, int R, int MT, int EPI, int NCH, int POLICY = 0>
 static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split, size_t split_stride,
                        int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
@@ -451,9 +465,10 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
         attr_done = true;
     }
     const int tiles = N / 32, per_wg = WN * R;
-    dim3 grid((tiles + per_wg - 1) / per_wg, m_chunks, split);
+    const int n_blocks = (tiles + per_wg - 1) / per_wg;
+    dim3 grid(n_blocks * m_chunks * split);
     hipLaunchKernelGGL(kern, grid, dim3(WN * WK * 64), smem, st, X, Wp, out, M, N, K, K, K / split, split_stride,
-                       mask_id, n_tiles_out);
+                       mask_id, n_tiles_out, n_blocks, split, m_chunks);
     return true;
 }
 

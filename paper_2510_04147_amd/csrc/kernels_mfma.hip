@@ -121,7 +121,7 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
                                                                int max_seqs, int seq_stride, int vt_rows, float scale,
                                                                const float* __restrict__ part, int n_part,
                                                                size_t part_stride, const float* __restrict__ cosT,
-                                                               const float* __restrict__ sinT) {
+                                                               const float* __restrict__ sinT, int nodes_per_seq) {
     constexpr int KST = DH / 16, DT = DH / 32;
     constexpr int NE = DT * 16;                                      // O^T values per lane
     constexpr int EPW = NE / ATTN_WAVES;                             // of which each wave merges EPW
@@ -134,16 +134,21 @@ __global__ __launch_bounds__(ATTN_WAVES * 64) void k_attn_mfma(const FwdHeader* 
     bf16_t* vs_own = ks_own + 32 * DH;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lm = lane & 31, lh = lane >> 5;
-    // Work-groups go to the 8 XCDs round-robin by their linear id, and every XCD has an L2 of its
-    // own: all (node, query head) pairs that read one KV head are placed on the same XCD, so the
-    // prefix is fetched from HBM once and the other nodes hit in L2.
+    // Work-groups go to the 8 XCDs round-robin by their linear id, and every XCD has an L2 of its own.
+    // The (node, query head) pairs that read the same keys and values form a class: the nodes of one
+    // sequence (nodes_per_seq consecutive nodes; 0: all nodes of the launch) times the query heads of one
+    // KV head.  Whole classes are placed on one XCD, so a sequence's prefix crosses the fabric once per
+    // KV head and the other members of the class hit in that L2.  Needs a class count divisible by 8;
+    // otherwise the plain order.
     const int n_nodes = gridDim.x / Hq, G = Hq / Hkv;
+    const int nps = nodes_per_seq > 0 ? nodes_per_seq : n_nodes;
+    const int n_classes = (n_nodes / nps) * Hkv, members = nps * G;
     int node, head;
-    if (Hkv % 8 == 0) {
+    if (n_classes % 8 == 0) {
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        node = slot % n_nodes;
-        const int rest = slot / n_nodes;
-        head = ((rest / G) * 8 + xcd) * G + rest % G;
+        const int cls = (slot / members) * 8 + xcd, mem = slot % members;
+        node = (cls / Hkv) * nps + mem % nps;
+        head = (cls % Hkv) * G + mem / nps;
     } else {
         node = blockIdx.x % n_nodes;
         head = blockIdx.x / n_nodes;
@@ -403,7 +408,9 @@ bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen) {
     return c->dm.dtype == SSD_BF16 && c->dm.dh == 128 && max_blen <= 32;
 }
 
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, bool suffix, hipStream_t st) {
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int nodes_per_seq, int max_blen, int layer, int n_part, bool suffix,
+                      hipStream_t st) {
+    if (nodes_per_seq <= 0 || n_nodes % nodes_per_seq) nodes_per_seq = 0;
     const Dims& d = c->dm;
     dim3 grid(n_nodes * d.Hq, (max_blen + 31) / 32);
     const float scale = 1.0f / sqrtf((float)d.dh);
@@ -411,7 +418,7 @@ bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, in
 #define SSD_ATTN_ARGS                                                                                                  \
     c->b.fwd, (const bf16_t*)c->b.q, (const bf16_t*)c->b.kown, (const bf16_t*)c->b.vown, (const bf16_t*)c->b.kcache, \
         (const bf16_t*)c->b.vcache, (bf16_t*)c->b.attn, d.Hq, d.Hkv, layer, d.max_seqs, d.seq_stride(), d.vt_rows(), scale, \
-        c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin
+        c->b.part, n_part, ps, c->b.rope_cos, c->b.rope_sin, nodes_per_seq
 #define SSD_ATTN_LAUNCH(DH_, FUSED_)                                                                       \
     do {                                                                                                   \
         if (suffix) k_attn_mfma<DH_, FUSED_, true><<<grid, ATTN_WAVES * 64, 0, st>>>(SSD_ATTN_ARGS);      \

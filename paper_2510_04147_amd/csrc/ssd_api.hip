@@ -498,6 +498,29 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
         any_suffix |= hd.nodes[i].T > hd.nodes[i].S + hd.nodes[i].blen;
     }
 
+    // nodes per sequence, if every sequence of the forward has equally many, consecutive in the node list
+    // (the attention launch then keeps the nodes and query heads that share a sequence's KV head on one XCD)
+    int nodes_per_seq = 0;
+    {
+        int run = 0, first_run = 0;
+        bool uniform = true;
+        for (int i = 0; i < hd.n_nodes; ++i) {
+            ++run;
+            if (i + 1 == hd.n_nodes || hd.nodes[i + 1].seq != hd.nodes[i].seq) {
+                if (first_run == 0) first_run = run;
+                uniform &= run == first_run;
+                run = 0;
+            }
+        }
+        // a sequence may appear only once as a run (decode groups first, then its KV-append group: not uniform)
+        bool seen[SSD_MAX_SEQS] = {};
+        for (int i = 0; uniform && i < hd.n_nodes; i += first_run) {
+            uniform &= !seen[hd.nodes[i].seq];
+            seen[hd.nodes[i].seq] = true;
+        }
+        if (uniform) nodes_per_seq = first_run;
+    }
+
     // ---- the kernel sequence: a function of (M, ML, n_nodes, n_groups, max_blen, kernel path) only
     auto launch_all = [&]() {
         {
@@ -523,7 +546,7 @@ static int run_forward(ssd_ctx* c, const FwdHeader& hd, const int32_t* raw, int 
             {
                 ProfScope ps(c, KC_ATTN);
                 if (!(c->kernel_path >= 1 && d.dtype == SSD_BF16 &&
-                      launch_attn_mfma(c, hd.n_nodes, max_blen, l, fused ? ns : -1, any_suffix, st)))
+                      launch_attn_mfma(c, hd.n_nodes, nodes_per_seq, max_blen, l, fused ? ns : -1, any_suffix, st)))
                     launch_attn_plain(c, M, l, st);
             }
             gemm(c, KC_GEMM_O, EPI_F32, c->b.attn, w.wo, c->b.part, M, &ns);
@@ -1181,7 +1204,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_k_attention(ssd_ctx* c
                                  hipMemcpyDeviceToDevice, st));
     launch_build_rows(c, st, hd.n_nodes);
     if (!fused) launch_rope(c, hd.n_nodes, max_blen, layer, n_part, st);
-    if (!(mfma && launch_attn_mfma(c, hd.n_nodes, max_blen, layer, fused ? n_part : -1, any_suffix, st)))
+    if (!(mfma && launch_attn_mfma(c, hd.n_nodes, 0, max_blen, layer, fused ? n_part : -1, any_suffix, st)))
         launch_attn_plain(c, M, layer, st);
     HIPCHK(c, hipMemcpyAsync(out_attn, c->b.attn, (size_t)M * d.nq() * d.esz(), hipMemcpyDeviceToDevice, st));
     if (out_q) HIPCHK(c, hipMemcpyAsync(out_q, c->b.q, (size_t)M * d.nq() * d.esz(), hipMemcpyDeviceToDevice, st));

@@ -261,5 +261,7 @@ bool launch_gemm_mfma_f32(const ssd_ctx* c, const uint16_t* x, const uint4* wp, 
 // n_part >= 0: the kernel also sums the QKV projection's n_part partial sums and applies the rotary
 // embedding itself (nodes of at most 32 rows, head size 128, no cache append); n_part < 0: q / kown / vown are ready
 // suffix: some node of the forward sees cached positions behind its block (NodeDesc::T)
-bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int max_blen, int layer, int n_part, bool suffix, hipStream_t st);
+// nodes_per_seq: nodes of every sequence of the forward if all have equally many (consecutive in the node list), else 0
+bool launch_attn_mfma(const ssd_ctx* c, int n_nodes, int nodes_per_seq, int max_blen, int layer, int n_part, bool suffix,
+                      hipStream_t st);
 bool attn_mfma_can_fuse_rope(const ssd_ctx* c, int max_blen);

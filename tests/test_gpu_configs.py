@@ -38,6 +38,48 @@ def test_cfg3_block64_depth8(w8b):
     eng.close()
 
 
+@pytest.mark.parametrize("M", [576, 200, 401])
+def test_many_row_gemm_gives_the_bits_of_the_few_row_gemm(w8b, M):
+    """Forwards with more than 192 rows run the GEMMs in several row chunks (work-groups of neighbouring
+    chunks share an n-block's weights).  Every linear step at M rows: against an fp64 product of the same
+    operands, and bit for bit against the same rows sent through in passes of at most 160 rows."""
+    from paper_2510_04147_amd import binding as B
+    cfg, w, wg = w8b
+    eng = B.SSD(cfg, wg, max_seqs=1, max_seq_len=256, block=64, max_draft=8, max_rows=640)
+    d, F = cfg["d_model"], cfg["d_ffn"]
+    g = torch.Generator(device="cuda").manual_seed(M)
+    lw = w["layers"][1]
+    try:
+        for which, W, K, N in ((B.LIN_QKV, lw["wqkv"], d, 3 * d), (B.LIN_O, lw["wo"], d, d), (B.LIN_DOWN, lw["wdown"], F, d)):
+            x = torch.randn(M, K, generator=g, device="cuda").to(torch.bfloat16)
+            out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+            eng.k_linear(which, 1, x, out)
+            err = (out.cpu().double() - x.cpu().double() @ W.double().T).abs().max().item()
+            assert err < 2e-4 * max(1.0, (K / 4096) ** 0.5), (which, err)
+            for lo in range(0, M, 160):
+                part = torch.empty(min(160, M - lo), N, dtype=torch.float32, device="cuda")
+                eng.k_linear(which, 1, x[lo:lo + 160].contiguous(), part)
+                assert torch.equal(part, out[lo:lo + 160]), (which, lo)
+        x = torch.randn(M, d, generator=g, device="cuda").to(torch.bfloat16)
+        out = torch.empty(M, F, dtype=torch.bfloat16, device="cuda")
+        eng.k_linear(B.LIN_GU, 1, x, out)
+        gu = x.cpu().double() @ lw["wgu"].double().T
+        want = gu[:, :F] / (1 + torch.exp(-gu[:, :F])) * gu[:, F:]
+        assert bool(((out.cpu().double() - want).abs() <= 2.0 ** -8 * want.abs() + 1e-4).all())
+        lm = torch.empty(3, M, dtype=torch.float32, device="cuda")
+        eng.k_linear(B.LIN_LM, 0, x, lm)
+        for lo in range(0, M, 160):
+            n = min(160, M - lo)
+            part = torch.empty(n, F, dtype=torch.bfloat16, device="cuda")
+            eng.k_linear(B.LIN_GU, 1, x[lo:lo + 160].contiguous(), part)
+            assert torch.equal(part, out[lo:lo + n]), ("gate/up", lo)
+            lmp = torch.empty(3, n, dtype=torch.float32, device="cuda")
+            eng.k_linear(B.LIN_LM, 0, x[lo:lo + 160].contiguous(), lmp)
+            assert torch.equal(lmp, lm[:, lo:lo + n]), ("lm head", lo)
+    finally:
+        eng.close()
+
+
 def test_cfg4_batch4_long_prefix(w8b):
     from paper_2510_04147_amd import binding
     cfg, w, wg = w8b

@@ -35,6 +35,14 @@
                reaches past the next refresh, so SSD and stepwise decoding refresh
                at the same states and stay identical.
 
+  spill-over   ssd_dual_spill: SSD with the dual cache whose chain continues into the next block
+               (Section 3.2.2: only when the current block has fewer than N positions left are
+               further positions taken from the next block).  Drafts for a block nobody has
+               predicted yet are read off the last refresh, whose forward covers every masked
+               position of the sequence.  Between refreshes a block is computed against the
+               cached keys and values of all other positions, so the next block's candidate
+               states can be evaluated in the same forward as the current block's.
+
   limit probe  acceptance_limit_probe: the procedure behind Table 2 (Section 5.1).
                Stepwise decoding is cut into rounds of N+1 steps (a new round at every
                block start); the logits of a round's first forward are what a draft
@@ -457,6 +465,123 @@ def ssd_dual(w, cfg, prompt, gen_len, block, n_draft, refresh, dtype=torch.float
                 x[S + q] = d
             since += len(accepted)
             drafts = next_drafts
+    return x[P:], dict(forwards=forwards, refreshes=refreshes, accept_hist=hist)
+
+
+def ssd_dual_spill(w, cfg, prompt, gen_len, block, n_draft, refresh, dtype=torch.float64, trace=None):
+    """SSD with the dual cache and spill-over selection (Section 3.2.2; Section 4.1 for the cache).
+
+    As ssd_dual, with two differences.
+    (1) While a next block exists the chain may hold drafts for ALL remaining positions of the current
+        block; if draft slots are left (at most n_draft drafts per round, and no round decodes past the
+        next refresh) the chain goes on in the next block: its first node there is the next block all
+        masked, the following ones have the next block's drafts written in.  Between refreshes a block's
+        forward sees every other position through the cache of the last refresh, so those nodes are
+        exactly the states stepwise decoding reaches once the current block is complete, and they run in
+        the same forward.  The walk crosses the boundary only if every draft of the current block
+        verified; at most one boundary per round; the leaf always keeps a position to predict.
+    (2) A block that no verification node has predicted yet takes its drafts from the last refresh,
+        whose forward covers every masked position of the sequence: all its positions by descending
+        confidence.  A block therefore starts with a full chain instead of a one-node forward.
+    Returns (tokens, stats) as ssd_dual."""
+    P, mask_id = len(prompt), cfg["mask_id"]
+    x = list(prompt) + [mask_id] * gen_len
+    blocks = _blocks(gen_len, block)
+    forwards = refreshes = 0
+    hist = [0] * (n_draft + 2)
+    since = None
+    K = V = refresh_logits = None
+
+    def from_refresh(bj):
+        """Drafts for block bj (all masked at the last refresh) read off that refresh's logits."""
+        off, Bn = blocks[bj]
+        t, _, c, _ = predict(refresh_logits[P + off:P + off + Bn], mask_id)
+        return [(q, int(t[q])) for q in rank_positions(c, [True] * Bn)]
+
+    def walk(nodes, preds, drafts):
+        """Chain walk: node m's stepwise choice must equal draft m+1.  Returns (m, p, t): m drafts matched and the
+        choice (p, t) of node m, or (m, None, None) if the chain has no node m (it ends with its last draft)."""
+        m = 0
+        while m < len(nodes):
+            p = stepwise_choice(preds[m][2], nodes[m][1])
+            t = int(preds[m][0][p])
+            if m < len(drafts) and (p, t) == (drafts[m][0], int(drafts[m][1])):
+                m += 1
+                continue
+            return m, p, t
+        return m, None, None
+
+    bi, drafts, predicted = 0, [], False       # predicted: the drafts come from a node of the current block
+    while bi < len(blocks):
+        off, Bj = blocks[bi]
+        S = P + off
+        tok = x[S:S + Bj]
+        masked = [t == mask_id for t in tok]
+        has_next = bi + 1 < len(blocks)
+        r = sum(masked)
+        is_refresh = since is None or since >= refresh
+        crossing, nodes_n, preds_n, nd = False, [], [], []
+        if is_refresh:
+            refresh_logits, K, V = _refresh(w, cfg, x, dtype)
+            nodes, preds, used = [(list(tok), list(masked))], [predict(refresh_logits[S:S + Bj], mask_id)], []
+            refreshes += 1
+            since = 0
+        else:
+            if not predicted:
+                drafts = from_refresh(bi) if all(masked) else []
+            budget = min(n_draft, refresh - since - 1)
+            a = max(0, min(len(drafts), budget, r if has_next else r - 1))
+            used = drafts[:a]
+            crossing = has_next and a == r
+            nodes = build_chain(tok, masked, used)
+            if crossing:
+                nodes = nodes[:-1]                                  # the complete block has nothing left to predict
+                Bn = blocks[bi + 1][1]
+                nd = from_refresh(bi + 1)[:max(0, min(budget - a, Bn - 1))]
+                nodes_n = build_chain([mask_id] * Bn, [True] * Bn, nd)
+                preds_n = [predict(forward_block_dual(w, cfg, nt, S + Bj, K, V, dtype), mask_id) for (nt, _) in nodes_n]
+            preds = [predict(forward_block_dual(w, cfg, nt, S, K, V, dtype), mask_id) for (nt, _) in nodes]
+        forwards += 1
+        # ---- the walk: the current block's nodes, then (if all of its drafts verified) the next block's
+        m, p, t = walk(nodes, preds, used)
+        crossed = p is None                     # only a chain that ends with its last draft (crossing) can run off its end
+        assert crossed <= crossing
+        if not crossed:
+            accepted = [(q, int(d)) for (q, d) in used[:m]] + [(p, t)]
+            for (q, d) in accepted:
+                assert x[S + q] == mask_id
+                x[S + q] = d
+            rest_mask = [x[S + q] == mask_id for q in range(Bj)]
+            rest = rank_positions(preds[m][2], rest_mask)
+            n_next = min(n_draft, len(rest) if has_next else max(len(rest) - 1, 0))
+            drafts, predicted = [(q, int(preds[m][0][q])) for q in rest[:n_next]], True
+            if not any(rest_mask):
+                bi += 1
+                drafts, predicted = [], False
+        else:
+            for (q, d) in used:
+                assert x[S + q] == mask_id
+                x[S + q] = d
+            k, p2, t2 = walk(nodes_n, preds_n, nd)
+            S2, Bn = S + Bj, blocks[bi + 1][1]
+            acc_n = [(q, int(d)) for (q, d) in nd[:k]] + [(p2, t2)]
+            for (q, d) in acc_n:
+                assert x[S2 + q] == mask_id
+                x[S2 + q] = d
+            accepted = [(q, int(d)) for (q, d) in used] + [(Bj + q, d) for (q, d) in acc_n]   # positions from the current block's start
+            bi += 1
+            rest_mask = [x[S2 + q] == mask_id for q in range(Bn)]
+            rest = rank_positions(preds_n[k][2], rest_mask)
+            n_next = min(n_draft, len(rest) if bi + 1 < len(blocks) else max(len(rest) - 1, 0))
+            drafts, predicted = [(q, int(preds_n[k][0][q])) for q in rest[:n_next]], True
+            if not any(rest_mask):
+                bi += 1
+                drafts, predicted = [], False
+        if trace is not None:
+            trace.append(dict(S=S, refresh=is_refresh, used=list(used), next_used=list(nd), crossed=crossed,
+                              accepted=list(accepted), nodes=len(nodes) + len(nodes_n)))
+        hist[len(accepted)] += 1
+        since += len(accepted)
     return x[P:], dict(forwards=forwards, refreshes=refreshes, accept_hist=hist)
 
 

@@ -667,3 +667,60 @@ def test_operand_noise_floor_equals_the_stored_value():
         assert abs(mod.sigma() - stored[0]) > 1e-3 * stored[0]
     finally:
         model.attention = orig
+
+
+# --------------------------------------------------------------------------
+# spill-over selection with the dual cache (Section 3.2.2 + Section 4.1): ssd_dual_spill
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("refresh", [1, 3, 8, 16, 100])
+@pytest.mark.parametrize("block,N", [(8, 4), (5, 3), (32, 4), (8, 6)])
+def test_spill_over_is_token_identical_to_stepwise_dual(tiny, refresh, block, N):
+    """Lossless for every refresh interval and block size, never more forwards than the in-block chain,
+    every round accepts between 1 and N + 1 tokens, refreshes at the same moments as stepwise decoding."""
+    cfg, w = tiny
+    prompt = synth.gen_prompt(cfg, 300 + refresh, 21)
+    gen = 40 if block != 32 else 64
+    base, s0 = decode.stepwise_dual(w, cfg, prompt, gen, block, refresh)
+    inb, s1 = decode.ssd_dual(w, cfg, prompt, gen, block, N, refresh)
+    trace = []
+    out, s2 = decode.ssd_dual_spill(w, cfg, prompt, gen, block, N, refresh, trace=trace)
+    assert out == base == inb
+    assert s2["refreshes"] == s0["refreshes"]
+    assert s2["forwards"] <= s1["forwards"] <= s0["forwards"] == gen
+    assert s2["accept_hist"][0] == 0 and sum(a * n for a, n in enumerate(s2["accept_hist"])) == gen
+    assert all(1 <= len(r["accepted"]) <= N + 1 and r["nodes"] <= N + 1 for r in trace)
+    assert all(len(r["accepted"]) == 1 and r["nodes"] == 1 for r in trace if r["refresh"])
+
+
+def test_spill_over_crosses_block_boundaries_and_saves_forwards(tiny):
+    """On a model whose drafts mostly verify (attention scaled down, not zeroed: positions still interact)
+    rounds do cross the boundary, and fewer forwards are needed than with the in-block chain."""
+    cfg, w = tiny
+    w2 = {k: v for k, v in w.items() if k != "layers"}
+    w2["layers"] = [dict(lw, wo=lw["wo"] * 0.02) for lw in w["layers"]]
+    prompt = synth.gen_prompt(cfg, 77, 16)
+    base, _ = decode.stepwise_dual(w2, cfg, prompt, 48, 8, 16)
+    inb, s1 = decode.ssd_dual(w2, cfg, prompt, 48, 8, 4, 16)
+    trace = []
+    out, s2 = decode.ssd_dual_spill(w2, cfg, prompt, 48, 8, 4, 16, trace=trace)
+    assert out == base == inb
+    assert any(r["crossed"] for r in trace)
+    assert s2["forwards"] < s1["forwards"]
+
+
+@pytest.mark.parametrize("N,refresh,block,gen", [(4, 8, 8, 48), (3, 8, 8, 40), (4, 16, 8, 48), (5, 12, 6, 48), (4, 8, 32, 64),
+                                                 (2, 5, 8, 43)])
+def test_spill_over_closed_form_with_zero_attention(tiny, N, refresh, block, gen):
+    """All wo = 0: every position ties, the order is left to right, every draft verifies, also those read off
+    the refresh.  Block boundaries then cost nothing: every refresh period of R tokens takes the refresh
+    forward (one token) plus ceil((R - 1) / (N + 1)) rounds, whatever the block length."""
+    cfg, w = tiny
+    w0 = {k: v for k, v in w.items() if k != "layers"}
+    w0["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in w["layers"]]
+    prompt = synth.gen_prompt(cfg, 5, 10)
+    base, _ = decode.stepwise_dual(w0, cfg, prompt, gen, block, refresh)
+    out, st = decode.ssd_dual_spill(w0, cfg, prompt, gen, block, N, refresh)
+    assert out == base and len(set(out)) == 1
+    full, rem = divmod(gen, refresh)
+    want = full * (1 + math.ceil((refresh - 1) / (N + 1))) + ((1 + math.ceil((rem - 1) / (N + 1))) if rem else 0)
+    assert st["forwards"] == want and st["refreshes"] == full + (1 if rem else 0)

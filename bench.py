@@ -249,6 +249,9 @@ def main():
             eng.set_cache_mode(1, 8)
             toks_d, st_d = eng.generate(prompts, G, B, N)
             toks_d0, st_d0 = eng.generate(prompts, G, B, 0)
+            eng.set_spill_over(1)                                # the chain continues into the next block (Section 3.2.2)
+            toks_ds, st_ds = eng.generate(prompts, G, B, N)
+            eng.set_spill_over(0)
             eng.set_cache_mode(0)
             # the acceptance-rate limit of self-drafting (Section 5.1, the procedure of Table 2), first sequence
             _, lim = eng.acceptance_limit(prompts[0], G, B, N, 5)
@@ -268,7 +271,10 @@ def main():
                                 stepwise_tokens_per_s=GT / (st_d0["total_ms"] / 1e3), ssd_forwards=st_d["forwards"],
                                 stepwise_forwards=st_d0["forwards"], refreshes=st_d["kv_passes"],
                                 accept_hist=st_d["accept_hist"][:N + 2],
-                                ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0))),
+                                spill_over_tokens_per_s=GT / (st_ds["total_ms"] / 1e3),
+                                spill_over_forwards=st_ds["forwards"], spill_over_accept_hist=st_ds["accept_hist"][:N + 2],
+                                ssd_equals_stepwise=bool(np.array_equal(toks_d, toks_d0) and
+                                                         np.array_equal(toks_ds, toks_d0))),
                 acceptance_limit=dict(draft_length=N, reduction_top_k=[round(x, 4) for x in lim["reduction"]],
                                       upper_bound=N / (N + 1), rounds=lim["rounds"]))
             # ---- the other acceptance extreme: the same model with every attention output projection zeroed.

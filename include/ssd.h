@@ -230,6 +230,19 @@ int ssd_set_cross_block(ssd_ctx* ctx, int on);
  * is also counted in stats.forwards.  Returns the previous mode or an error. */
 int ssd_set_cache_mode(ssd_ctx* ctx, int mode, int refresh_interval);
 
+/* Spill-over selection in ssd_generate with the dual cache (Section 3.2.2: once the current block has fewer
+ * positions left than the draft length, further candidates come from the next block).  1 = while a next block
+ * exists the chain may hold drafts for every remaining position of the current block and then goes on in the
+ * next block: that block all masked, then with its drafts written in, in the same forward (between refreshes a
+ * block sees all other positions through the cache, so those are the states stepwise decoding reaches once the
+ * current block is complete).  The next block's drafts, and those of any block nobody has predicted yet, are
+ * its positions by descending confidence of the last refresh, whose forward covers every masked position: a
+ * block then starts with a full chain instead of a one-node forward.  A round still never decodes past the
+ * next refresh, so the generated tokens are those of stepwise decoding; at most one block boundary per round.
+ * Only with cache mode 1 and the greedy chain; the step calls (ssd_refresh_kv, ssd_verify_tree) are not
+ * affected.  Default 0.  Returns the previous value or an error. */
+int ssd_set_spill_over(ssd_ctx* ctx, int on);
+
 /* One cache refresh of the dual cache (Section 4.1) for sequence `seq`, as a call of its own:
  * tokens[0..total_len) (host) is the whole sequence, mask id at every position not decoded yet;
  * the current block is [pos0, pos0 + block_len) and must hold at least one mask.  Runs all

@@ -21,7 +21,7 @@ SSD_F32, SSD_BF16 = 0, 1
 
 EXPORTS = ["ssd_workspace_bytes", "ssd_create", "ssd_destroy", "ssd_reset", "ssd_cached_len", "ssd_prefill_kv",
            "ssd_draft", "ssd_verify_tree", "ssd_generate", "ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_graphs", "ssd_set_tree_mode", "ssd_set_cross_block",
-           "ssd_set_cache_mode", "ssd_refresh_kv", "ssd_acceptance_limit",
+           "ssd_set_cache_mode", "ssd_set_spill_over", "ssd_refresh_kv", "ssd_acceptance_limit",
            "ssd_profile_begin",
            "ssd_profile_read", "ssd_profile_end", "ssd_strerror", "ssd_last_error", "ssd_k_linear", "ssd_k_accept", "ssd_k_lm_head_static",
            "ssd_k_write_cache", "ssd_k_attention", "ssd_k_norm"]
@@ -87,6 +87,7 @@ def load_library() -> C.CDLL:
     lib.ssd_set_tree_mode.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cross_block.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_set_cache_mode.argtypes = [C.c_void_p, C.c_int, C.c_int]
+    lib.ssd_set_spill_over.argtypes = [C.c_void_p, C.c_int]
     lib.ssd_acceptance_limit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ssd_refresh_kv.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -245,6 +246,9 @@ class SSD:
 
     def set_cache_mode(self, mode, refresh_interval=0):
         return self._chk(self.lib.ssd_set_cache_mode(self.h, int(mode), int(refresh_interval)))
+
+    def set_spill_over(self, on):
+        return self._chk(self.lib.ssd_set_spill_over(self.h, int(on)))
 
     def refresh_kv(self, seq, tokens, pos0, block_len, n_draft_next, out):
         t = _i32(tokens)

@@ -38,12 +38,29 @@ __device__ __forceinline__ float wave_max(float v) {
 __global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restrict__ state,
                              const int* __restrict__ raw_tok, int* __restrict__ row_tok,
                              int* __restrict__ row_pos, int* __restrict__ row_node,
-                             int* __restrict__ out_tok, int mask_id, int max_seq_len) {
+                             int* __restrict__ out_tok, int mask_id, int max_seq_len,
+                             const float* __restrict__ ref_conf, const int* __restrict__ ref_arg) {
     const int ni = blockIdx.x;
     if (ni >= fw->n_nodes) return;
     const NodeDesc nd = fw->nodes[ni];
     const GroupDesc g = fw->groups[nd.group];
     SeqState* s = &state[nd.seq];
+    // A block nobody has predicted yet, with drafts read off the last refresh (Section 3.2.2 with the cache of
+    // Section 4.1): node j holds the j positions the refresh was most confident of.  One wave per node, one lane
+    // per position.
+    int ref_rank = 0x7fffffff, ref_tok = mask_id;
+    if (g.mode == GM_DECODE && g.from_refresh) {             // uniform over the wave
+        const int lane = threadIdx.x;
+        const size_t base = (size_t)nd.seq * max_seq_len + nd.S;
+        const float c = lane < nd.blen ? ref_conf[base + lane] : -1.f;
+        int rank = 0;
+        for (int qd = 0; qd < 64; ++qd) {
+            const float cq = __shfl(c, qd, 64);
+            if (qd < nd.blen && (cq > c || (cq == c && qd < lane))) ++rank;
+        }
+        ref_rank = rank;
+        if (lane < nd.blen) ref_tok = ref_arg[base + lane];
+    }
     for (int p = threadIdx.x; p < nd.blen; p += blockDim.x) {
         int tok;
         if (g.mode == GM_RAW) {
@@ -51,6 +68,8 @@ __global__ void k_build_rows(const FwdHeader* __restrict__ fw, SeqState* __restr
         } else if (g.mode == GM_APPEND) {
             tok = s->tok[p];
             if (g.out_off >= 0) out_tok[(size_t)nd.seq * max_seq_len + g.out_off + p] = tok;
+        } else if (g.from_refresh) {
+            tok = ref_rank < nd.j ? ref_tok : mask_id;       // a decode block has at most 64 positions: p is this lane
         } else if (g.fresh) {
             tok = mask_id;
         } else {
@@ -497,16 +516,43 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
                                                const float* __restrict__ row_conf, const int* __restrict__ row_arg,
                                                const float* __restrict__ row_max, StepResult* __restrict__ result,
                                                int* __restrict__ out_tok, int max_seq_len, int blockB, int maxDraft,
-                                               int mask_id) {
+                                               int mask_id, float* __restrict__ ref_conf, int* __restrict__ ref_arg) {
     const int gi = blockIdx.x, lane = threadIdx.x;
     const GroupDesc g = fw->groups[gi];
     const ssd_step_out out = fw->out;
+    if (g.mode == GM_RAW && g.keep_ref) {
+        // rows of a cache refresh behind the current block: their predictions are the drafts later blocks
+        // start from (Section 3.2.2: candidates from the next block; Section 4.1: the refresh covers all positions)
+        for (int p = lane; p < g.blen; p += 64) {
+            ref_conf[(size_t)g.seq * max_seq_len + g.S + p] = row_conf[g.row0 + p];
+            ref_arg[(size_t)g.seq * max_seq_len + g.S + p] = row_arg[g.row0 + p];
+        }
+        return;
+    }
     if (g.mode != GM_DECODE || g.spec_of1 != 0) return;   // a speculative group is its master's business
     SeqState* s = &state[g.seq];
-    const int nd = g.n_chain - 1;                         // drafts = chain nodes - 1
+    // drafts = chain nodes - 1, or one per chain node if the node holding all of them was left out
+    const int nd = g.leafless ? g.n_chain : g.n_chain - 1;
     const int blen = g.blen;
-    const int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
-    const int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
+    __shared__ int sh_pos[64], sh_tok[64];
+    // drafts read off the last refresh: the block's positions by descending confidence; lane k gets draft k
+    auto drafts_from_refresh = [&](int S_blk, int blen_blk, int& dpos, int& dtok) {
+        const size_t base = (size_t)g.seq * max_seq_len + S_blk;
+        const float cr = lane < blen_blk ? ref_conf[base + lane] : -1.f;
+        int rank = 0;
+        for (int qd = 0; qd < 64; ++qd) {
+            const float cq = __shfl(cr, qd, 64);
+            if (qd < blen_blk && (cq > cr || (cq == cr && qd < lane))) ++rank;
+        }
+        __syncthreads();
+        if (lane < blen_blk) { sh_pos[rank] = lane; sh_tok[rank] = ref_arg[base + lane]; }
+        __syncthreads();
+        dpos = lane < blen_blk ? sh_pos[lane] : -1;
+        dtok = lane < blen_blk ? sh_tok[lane] : -1;
+    };
+    int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
+    int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
+    if (g.from_refresh) drafts_from_refresh(g.S, blen, my_dpos, my_dtok);
     // a fresh block starts all masked with no drafts (Algorithm 1, line 3); its state is written here,
     // at the end of the forward, so that a KV-append group of the same sequence in the same forward
     // still reads the finished block's tokens
@@ -514,7 +560,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     __syncthreads();
 
     if (lane < blen) {
-        for (int j = 0; j <= nd; ++j) {
+        for (int j = 0; j < g.n_chain && j <= maxDraft; ++j) {
             const int row = g.row0 + j * blen + lane;
             const size_t o = ((size_t)gi * (maxDraft + 1) + j) * blockB + lane;
             if (out.row_maxlogit) out.row_maxlogit[o] = row_max[row];
@@ -523,14 +569,13 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         }
     }
 
-    // stepwise choice of a node over the positions still masked in `cur`: highest confidence, ties to
-    // the lowest position; leaves this lane's confidence in c
+    // stepwise choice of a node (rows row0 + lane of a block of bl positions) over the positions still masked in
+    // `cur`: highest confidence, ties to the lowest position; leaves this lane's confidence in c
     int pstar = 0, tstar = 0;
     float c = -1.f;
-    auto choose = [&](int node) {
-        const int row = g.row0 + node * blen + lane;
-        const bool valid = lane < blen && ((cur >> lane) & 1ull);
-        c = valid ? row_conf[row] : -1.f;
+    auto choose_at = [&](int row0, int bl) {
+        const bool valid = lane < bl && ((cur >> lane) & 1ull);
+        c = valid ? row_conf[row0 + lane] : -1.f;
         float bc = c;
         int bp = lane;
 #pragma unroll
@@ -540,12 +585,13 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
             if (oc > bc || (oc == bc && op < bp)) { bc = oc; bp = op; }
         }
         pstar = bp;
-        tstar = row_arg[g.row0 + node * blen + pstar];
+        tstar = row_arg[row0 + pstar];
     };
+    auto choose = [&](int node) { choose_at(g.row0 + node * blen, blen); };
     int m = 0;
     bool complete = false;
     while (true) {
-        if (cur == 0ull) { complete = true; break; }     // the drafts covered every masked position: the leaf
+        if (cur == 0ull) { complete = true; break; }     // the drafts covered every masked position
         choose(m);
         const int dp = __shfl(my_dpos, m, 64), dt = __shfl(my_dtok, m, 64);
         if (m < nd && pstar == dp && tstar == dt) {
@@ -558,9 +604,13 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     StepResult* r = &result[g.seq];
     if (complete) {
         // Every draft verified and the block is finished (Section 3.2.2, the round across the block
-        // boundary).  Its tokens go to the output; its KV was written by the leaf in this forward.
-        // The group behind the leaf, if any, is the next block's block-start forward: its stepwise
-        // choice is one more accepted token and its other positions give the next drafts.
+        // boundary).  Its tokens go to the output (exact cache: its KV was written by the leaf in this
+        // forward).  The group behind it, if any, holds the next block: all masked, then with the drafts
+        // the last refresh gives it written in.  The walk goes on there: its matched drafts and the
+        // choice of the node it stops at are further accepted tokens (positions counted on from this
+        // block's length), and that node's other positions give the next drafts.
+        if (g.fresh) s->tok[lane] = mask_id;
+        __syncthreads();
         if (lane < m) {
             r->acc_pos[lane] = my_dpos;
             r->acc_tok[lane] = my_dtok;
@@ -571,26 +621,24 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         __syncthreads();
         if (g.out_off >= 0 && lane < blen) out_tok[(size_t)g.seq * max_seq_len + g.out_off + lane] = s->tok[lane];
         __syncthreads();
-        int n_acc = m, n_next = 0;
+        int n_acc = m, n_next = 0, n_in_next = 0;
         unsigned long long rem = 0ull;
         if (g.spec_next1 != 0) {
             const GroupDesc g2 = fw->groups[g.spec_next1 - 1];
-            const int blen2 = g2.blen;
+            const int blen2 = g2.blen, nd2 = g2.n_chain - 1;
+            int dpos2 = -1, dtok2 = -1;
+            if (g2.from_refresh) drafts_from_refresh(g2.S, blen2, dpos2, dtok2);
             cur = blen2 >= 64 ? ~0ull : ((1ull << blen2) - 1ull);
-            {   // stepwise choice of the next block's all-masked node
-                const int row = g2.row0 + lane;
-                const bool valid = lane < blen2;
-                c = valid ? row_conf[row] : -1.f;
-                float bc = c;
-                int bp = lane;
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const float oc = __shfl_xor(bc, off, 64);
-                    const int op = __shfl_xor(bp, off, 64);
-                    if (oc > bc || (oc == bc && op < bp)) { bc = oc; bp = op; }
+            int k = 0;
+            while (true) {
+                choose_at(g2.row0 + k * blen2, blen2);
+                const int dp = __shfl(dpos2, k, 64), dt = __shfl(dtok2, k, 64);
+                if (k < nd2 && pstar == dp && tstar == dt) {
+                    cur &= ~(1ull << pstar);
+                    ++k;
+                    continue;
                 }
-                pstar = bp;
-                tstar = row_arg[g2.row0 + pstar];
+                break;
             }
             rem = cur & ~(1ull << pstar);
             const int n_rem = __popcll(rem);
@@ -601,7 +649,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
                 const float cq = __shfl(c, qd, 64);
                 if (((rem >> qd) & 1ull) && (cq > c || (cq == c && qd < lane))) ++rank;
             }
-            const int my_tok = row_arg[g2.row0 + (lane < blen2 ? lane : 0)];
+            const int my_tok = row_arg[g2.row0 + k * blen2 + (lane < blen2 ? lane : 0)];
             if (mine && rank < n_next) {
                 r->next_pos[rank] = lane;
                 r->next_tok[rank] = my_tok;
@@ -612,19 +660,23 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
             }
             s->tok[lane] = mask_id;
             __syncthreads();
-            if (lane == 0) {
-                s->tok[pstar] = tstar;
-                r->acc_pos[m] = pstar;
-                r->acc_tok[m] = tstar;
-                if (out.acc_pos) out.acc_pos[(size_t)gi * (maxDraft + 1) + m] = pstar;
-                if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + m] = tstar;
+            if (lane <= k) {
+                // the next block's matched drafts, then the choice of the node the walk stopped at
+                const int ap = lane < k ? dpos2 : pstar, at = lane < k ? dtok2 : tstar;
+                s->tok[ap] = at;
+                r->acc_pos[m + lane] = blen + ap;
+                r->acc_tok[m + lane] = at;
+                if (out.acc_pos) out.acc_pos[(size_t)gi * (maxDraft + 1) + m + lane] = blen + ap;
+                if (out.acc_tok) out.acc_tok[(size_t)gi * (maxDraft + 1) + m + lane] = at;
             }
-            n_acc = m + 1;
+            n_in_next = k + 1;
+            n_acc = m + n_in_next;
         }
         if (lane == 0) {
             r->n_accept = n_acc;
             r->n_next = n_next;
             r->completed = 1;
+            r->n_in_next = n_in_next;
             s->masked = rem;
             s->n_draft = n_next;
             if (out.n_accept) out.n_accept[gi] = n_acc;
@@ -681,6 +733,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
         r->n_accept = n_acc;
         r->n_next = n_next;
         r->completed = 0;
+        r->n_in_next = 0;
         s->masked = rem;
         s->n_draft = n_next;
         if (out.n_accept) out.n_accept[gi] = n_acc;
@@ -693,7 +746,8 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
 // ------------------------------------------------------------------------
 void launch_build_rows(const ssd_ctx* c, hipStream_t st, int n_nodes) {
     k_build_rows<<<n_nodes, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.raw_tok, c->b.row_tok, c->b.row_pos,
-                                         c->b.row_node, c->b.out_tok, c->dm.mask_id, c->dm.max_seq_len);
+                                         c->b.row_node, c->b.out_tok, c->dm.mask_id, c->dm.max_seq_len, c->b.ref_conf,
+                                         c->b.ref_arg);
 }
 
 void launch_embed(const ssd_ctx* c, int M, hipStream_t st) {
@@ -779,7 +833,8 @@ void launch_lm_merge_to(const ssd_ctx* c, int M, int n_tiles, const float* part,
 
 void launch_accept(const ssd_ctx* c, int n_groups, hipStream_t st) {
     k_accept<<<n_groups, 64, 0, st>>>(c->b.fwd, c->b.state, c->b.row_conf, c->b.row_arg, c->b.row_max, c->b.result,
-                                      c->b.out_tok, c->dm.max_seq_len, c->dm.block, c->dm.max_draft, c->dm.mask_id);
+                                      c->b.out_tok, c->dm.max_seq_len, c->dm.block, c->dm.max_draft, c->dm.mask_id,
+                                      c->b.ref_conf, c->b.ref_arg);
 }
 
 // Helpers of the kernel-level entry points.

@@ -152,6 +152,8 @@ static size_t carve(const Dims& d, char* base, Buffers* b) {
     t.state = (SeqState*)take(sizeof(SeqState) * SSD_MAX_SEQS);
     t.result = (StepResult*)take(sizeof(StepResult) * SSD_MAX_SEQS);
     t.out_tok = (int*)take((size_t)d.max_seqs * d.max_seq_len * 4);
+    t.ref_conf = (float*)take((size_t)d.max_seqs * d.max_seq_len * 4);
+    t.ref_arg = (int*)take((size_t)d.max_seqs * d.max_seq_len * 4);
     t.probe_logits = (float*)take((size_t)d.block * d.V * 4);
     t.probe_rank = (int*)take((SSD_MAX_DRAFT + 1) * 4);
     t.lm_tiles = tiles;
@@ -229,6 +231,7 @@ extern "C" __attribute__((visibility("default"))) int ssd_create(const ssd_confi
     c->fuse_boundary = 1;
     c->tree_mode = 0;
     c->cross_block = 0;
+    c->spill_over = 0;
     c->cache_mode = 0;
     c->refresh_interval = 0;
     memset(c->total_len, 0, sizeof c->total_len);
@@ -324,6 +327,13 @@ extern "C" __attribute__((visibility("default"))) int ssd_set_cross_block(ssd_ct
     if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
     const int old = c->cross_block;
     c->cross_block = on;
+    return old;
+}
+
+extern "C" __attribute__((visibility("default"))) int ssd_set_spill_over(ssd_ctx* c, int on) {
+    if (!c || (on != 0 && on != 1)) return SSD_EINVAL;
+    const int old = c->spill_over;
+    c->spill_over = on;
     return old;
 }
 
@@ -615,7 +625,8 @@ static int add_group(FwdHeader& hd, int seq, int mode, int blen, int S, int n_ch
     const int n_nodes = n_chain + n_extra;
     g.seq = seq; g.row0 = hd.M; g.blen = blen; g.S = S; g.n_nodes = n_nodes; g.mode = mode; g.raw_off = raw_off;
     g.n_draft_next = n_draft_next; g.fresh = fresh; g.out_off = out_off; g.node0 = hd.n_nodes; g.n_chain = n_chain;
-    g.spec_next1 = 0; g.spec_of1 = 0; g.allow_full = allow_full; g.pad = 0;
+    g.spec_next1 = 0; g.spec_of1 = 0; g.allow_full = allow_full;
+    g.from_refresh = 0; g.leafless = 0; g.keep_ref = 0; g.pad[0] = g.pad[1] = 0;
     int vrows = hd.n_nodes ? hd.nodes[hd.n_nodes - 1].vrow0 + ((hd.nodes[hd.n_nodes - 1].blen + 63) & ~63) : 0;
     for (int j = 0; j < n_nodes; ++j) {
         NodeDesc& nd = hd.nodes[hd.n_nodes++];
@@ -805,6 +816,11 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
                          int draft_depth, int32_t* out_tokens, ssd_stats* stats) {
     const Dims& d = c->dm;
     const int R = c->refresh_interval > 0 ? c->refresh_interval : block;
+    // Spill-over (Section 3.2.2): while a next block exists the chain may hold drafts for every remaining
+    // position of the current block and then goes on in the next block, whose drafts are read off the last
+    // refresh; a block nobody has predicted yet starts with such drafts too.  Between refreshes a block's
+    // forward sees all other positions through the cache, so both blocks' nodes run in one forward.
+    const bool spill = c->spill_over != 0;
     long long rows_all = 0;
     for (int i = 0; i < n; ++i) rows_all += prompt_len[i] + gen_len;
     if (rows_all > d.max_rows) {
@@ -817,7 +833,6 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
     EventPair evp;
     HIPCHK(c, evp.create());
     const hipEvent_t ev0 = evp.a, ev1 = evp.b;
-    auto done = [&](int rc) { return rc; };
     const int n_blocks = (gen_len + block - 1) / block;
     std::vector<std::vector<int32_t>> x(n);
     int blk[SSD_MAX_SEQS], n_masked[SSD_MAX_SEQS], n_dr[SSD_MAX_SEQS], since[SSD_MAX_SEQS];
@@ -828,65 +843,131 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
         blk[i] = 0; n_masked[i] = 0; n_dr[i] = 0; since[i] = R; start[i] = true; live_seq[i] = true;
         c->total_len[i] = 0;
     }
+    auto block_len = [&](int b) { return std::min(block, gen_len - b * block); };
     int live = n, rc;
     std::vector<int32_t> raw;
     while (live > 0) {
         FwdHeader hd;
         memset(&hd, 0, sizeof hd);
         raw.clear();
+        int master_of[SSD_MAX_SEQS], keep_end[SSD_MAX_SEQS];
         for (int i = 0; i < n; ++i) {                       // decode groups first: their rows get logits
+            master_of[i] = -1;
+            keep_end[i] = 0;
             if (!live_seq[i]) continue;
-            const int S = prompt_len[i] + blk[i] * block, bl = std::min(block, gen_len - blk[i] * block);
+            const int S = prompt_len[i] + blk[i] * block, bl = block_len(blk[i]);
             const int T = prompt_len[i] + gen_len;
+            const bool has_next = blk[i] + 1 < n_blocks;
             if (start[i]) { n_masked[i] = bl; n_dr[i] = 0; }
             refresh_now[i] = since[i] >= R;
             c->cached_len[i] = S;
+            master_of[i] = hd.n_groups;
             if (refresh_now[i]) {
                 refresh_head(hd, i, S, bl, T, draft_depth, start[i]);
-            } else {
-                const int ndr = std::max(0, std::min(std::min(n_dr[i], n_masked[i] - 1), R - since[i] - 1));
-                add_group(hd, i, GM_DECODE, bl, S, ndr + 1, 0, draft_depth, start[i], 0, -1, 0, false, T);
+                hd.groups[master_of[i]].allow_full = spill && has_next;
+                continue;
             }
+            const int budget = std::min(draft_depth, R - since[i] - 1);
+            if (!spill) {
+                const int ndr = std::max(0, std::min(std::min(n_dr[i], n_masked[i] - 1), budget));
+                add_group(hd, i, GM_DECODE, bl, S, ndr + 1, 0, draft_depth, start[i], 0, -1, 0, false, T);
+                continue;
+            }
+            // drafts at hand: the last node's, or (a block nobody predicted yet) all positions ranked by the refresh
+            const int avail = start[i] ? bl : n_dr[i];
+            const int a = std::max(0, std::min(std::min(avail, budget), has_next ? n_masked[i] : n_masked[i] - 1));
+            const bool crossing = has_next && a == n_masked[i];
+            add_group(hd, i, GM_DECODE, bl, S, crossing ? a : a + 1, 0, draft_depth, start[i], 0, -1, has_next, false, T);
+            hd.groups[master_of[i]].from_refresh = start[i];
+            hd.groups[master_of[i]].leafless = crossing;
+            if (crossing) {
+                const int bln = block_len(blk[i] + 1);
+                const int b = std::max(0, std::min(budget - a, bln - 1));
+                hd.groups[master_of[i]].spec_next1 = hd.n_groups + 1;
+                add_group(hd, i, GM_DECODE, bln, S + bl, b + 1, 0, draft_depth, 1, 0, -1, blk[i] + 2 < n_blocks, false, T);
+                hd.groups[hd.n_groups - 1].from_refresh = 1;
+                hd.groups[hd.n_groups - 1].spec_of1 = master_of[i] + 1;
+            }
+        }
+        // refreshes: the positions right behind the block, as far as decoding can get before the next refresh,
+        // keep their predictions (the drafts of the blocks entered until then); they need logits, so they follow
+        // the decode groups directly
+        for (int i = 0; spill && i < n; ++i) {
+            if (!live_seq[i] || !refresh_now[i]) continue;
+            const int S = prompt_len[i] + blk[i] * block, bl = block_len(blk[i]), T = prompt_len[i] + gen_len;
+            const int from = S + bl, upto = std::min(T, from + ((R + block - 1) / block + 1) * block);
+            if (upto <= from) continue;
+            add_group(hd, i, GM_RAW, upto - from, from, 1, 0, 0, 0, (int)raw.size(), -1, 0, false, T);
+            hd.groups[hd.n_groups - 1].keep_ref = 1;
+            raw.insert(raw.end(), x[i].begin() + from, x[i].begin() + upto);
+            hd.M_logits = hd.M;
+            keep_end[i] = upto;
         }
         for (int i = 0; i < n; ++i) {
             if (!live_seq[i] || !refresh_now[i]) continue;
-            const int S = prompt_len[i] + blk[i] * block, bl = std::min(block, gen_len - blk[i] * block);
-            refresh_tail(hd, i, x[i].data(), S, bl, prompt_len[i] + gen_len, raw);
-            c->total_len[i] = prompt_len[i] + gen_len;
+            const int S = prompt_len[i] + blk[i] * block, bl = block_len(blk[i]), T = prompt_len[i] + gen_len;
+            if (keep_end[i] > 0) {
+                // everything before the block, then what lies behind the kept positions
+                if (S > 0) {
+                    add_group(hd, i, GM_RAW, S, 0, 1, 0, 0, 0, (int)raw.size(), -1, 0, false, T);
+                    raw.insert(raw.end(), x[i].begin(), x[i].begin() + S);
+                }
+                if (T > keep_end[i]) {
+                    add_group(hd, i, GM_RAW, T - keep_end[i], keep_end[i], 1, 0, 0, 0, (int)raw.size(), -1, 0, false, T);
+                    raw.insert(raw.end(), x[i].begin() + keep_end[i], x[i].begin() + T);
+                }
+            } else {
+                refresh_tail(hd, i, x[i].data(), S, bl, T, raw);
+            }
+            c->total_len[i] = T;
         }
-        if (hd.M > d.max_rows) { set_err(c, "generate: forward exceeds max_rows"); return done(SSD_ERANGE); }
+        if (hd.M > d.max_rows) { set_err(c, "generate: forward exceeds max_rows"); return SSD_ERANGE; }
         (void)hipEventRecord(ev0, c->stream);
-        if ((rc = run_forward(c, hd, raw.data(), (int)raw.size(), nullptr, 0, nullptr)) != SSD_OK) return done(rc);
+        if ((rc = run_forward(c, hd, raw.data(), (int)raw.size(), nullptr, 0, nullptr)) != SSD_OK) return rc;
         HIPCHK(c, hipMemcpyAsync(c->host_result, c->b.result, sizeof(StepResult) * d.max_seqs, hipMemcpyDeviceToHost, c->stream));
         (void)hipEventRecord(ev1, c->stream);
-        if (hipEventSynchronize(ev1) != hipSuccess) { set_err(c, "generate: sync failed: %s", hipGetErrorString(hipGetLastError())); return done(SSD_EHIP); }
+        if (hipEventSynchronize(ev1) != hipSuccess) { set_err(c, "generate: sync failed: %s", hipGetErrorString(hipGetLastError())); return SSD_EHIP; }
         float ms = 0; (void)hipEventElapsedTime(&ms, ev0, ev1);
         sta.decode_ms += ms;
         sta.forwards++;
-        for (int gi = 0; gi < hd.n_groups; ++gi) {
-            const GroupDesc& g = hd.groups[gi];
-            if (g.mode != GM_DECODE) continue;
-            const int i = g.seq;
+        for (int i = 0; i < n; ++i) {
+            if (master_of[i] < 0) continue;
+            const GroupDesc& g = hd.groups[master_of[i]];
             const StepResult& r = c->host_result[i];
-            if (r.n_accept < 1 || r.n_accept > g.n_chain || r.n_accept > n_masked[i]) {
-                set_err(c, "generate: acceptance kernel returned %d for a chain of %d nodes", r.n_accept, g.n_chain);
-                return done(SSD_EHIP);
+            const int bln = g.spec_next1 ? hd.groups[g.spec_next1 - 1].blen : 0;
+            const int chain_next = g.spec_next1 ? hd.groups[g.spec_next1 - 1].n_chain : 0;
+            const bool crossed = r.completed != 0;
+            bool ok = r.n_accept >= 1 && r.n_accept <= SSD_MAX_DRAFT + 1;
+            if (crossed)
+                ok = ok && g.spec_next1 != 0 && g.leafless && r.n_in_next >= 1 && r.n_in_next <= chain_next &&
+                     r.n_accept == n_masked[i] + r.n_in_next;
+            else
+                ok = ok && r.n_accept <= g.n_chain && r.n_accept <= n_masked[i] && r.n_in_next == 0;
+            if (!ok) {
+                set_err(c, "generate: acceptance kernel returned %d tokens (%d in the next block) for a chain of %d + %d nodes",
+                        r.n_accept, r.n_in_next, g.n_chain, chain_next);
+                return SSD_EHIP;
             }
             for (int k = 0; k < r.n_accept; ++k) {
-                if (r.acc_pos[k] < 0 || r.acc_pos[k] >= g.blen) { set_err(c, "generate: accepted position out of range"); return done(SSD_EHIP); }
+                if (r.acc_pos[k] < 0 || r.acc_pos[k] >= g.blen + (crossed ? bln : 0)) { set_err(c, "generate: accepted position out of range"); return SSD_EHIP; }
                 x[i][(size_t)g.S + r.acc_pos[k]] = r.acc_tok[k];
             }
             sta.accept_hist[r.n_accept]++;
             sta.tokens += r.n_accept;
             if (refresh_now[i]) { since[i] = 0; sta.kv_passes++; }
             since[i] += r.n_accept;
-            n_masked[i] -= r.n_accept;
             n_dr[i] = r.n_next;
             start[i] = false;
+            if (crossed) {
+                blk[i]++;
+                n_masked[i] = bln - r.n_in_next;
+            } else {
+                n_masked[i] -= r.n_accept;
+            }
             if (n_masked[i] == 0) {
                 blk[i]++;
                 start[i] = true;
-                if (blk[i] == n_blocks) { live_seq[i] = false; live--; }
+                if (blk[i] >= n_blocks) { live_seq[i] = false; live--; }
             }
         }
     }
@@ -894,7 +975,7 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
         memcpy(out_tokens + (size_t)i * gen_len, x[i].data() + prompt_len[i], (size_t)gen_len * 4);
     sta.total_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     if (stats) *stats = sta;
-    return done(SSD_OK);
+    return SSD_OK;
 }
 
 // ------------------------------------------------------------- Algorithm 1

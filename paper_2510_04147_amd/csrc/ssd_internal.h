@@ -11,8 +11,9 @@
 #define SSD_MAX_SEQS 16
 // per sequence: the largest tree (2 * draft length nodes with mix order) plus a KV-append node
 #define SSD_MAX_NODES (SSD_MAX_SEQS * (2 * SSD_MAX_DRAFT + 1))
-// per sequence: a block's chain, the next block behind its leaf or a KV append, a cache refresh's three segments
-#define SSD_MAX_GROUPS (3 * SSD_MAX_SEQS)
+// per sequence: a block's chain, the next block behind its leaf or a KV append; a cache refresh's segments (the
+// block, the positions behind it whose predictions are kept, the rest behind, everything before)
+#define SSD_MAX_GROUPS (4 * SSD_MAX_SEQS)
 #define SSD_MAX_SPLIT 8
 
 // ---- forward descriptor (host-built, copied to the device before each forward)
@@ -35,7 +36,13 @@ struct GroupDesc {
     // its master's index + 1 and is handled by the master's work-group of the acceptance kernel.
     int spec_next1, spec_of1;
     int allow_full; // next drafts may cover every remaining masked position (a next block exists)
-    int pad;
+    // Spill-over with the dual cache (Section 3.2.2 + Section 4.1).  from_refresh: the block is all masked and
+    // nobody has predicted it yet; its drafts are its positions by descending confidence of the last refresh
+    // (ref_conf / ref_arg), n_chain - 1 of them (n_chain if leafless).  leafless: the chain's drafts cover every
+    // masked position and the node holding all of them is left out (between refreshes nothing reads it).
+    // keep_ref (a raw group of a refresh): the rows' predictions are kept as that refresh's drafts.
+    int from_refresh, leafless, keep_ref;
+    int pad[2];
 };
 
 struct NodeDesc {
@@ -69,8 +76,8 @@ struct SeqState {
 // by ssd_generate.
 struct StepResult {
     int n_accept, n_next;
-    int completed;  // the round verified drafts for every masked position: the block is finished and its KV cached
-    int pad;
+    int completed;  // the round verified drafts for every masked position: the block is finished (exact cache: and its KV cached)
+    int n_in_next;  // of the accepted tokens, those that lie in the next block (their acc_pos count on from this block's length)
     int acc_pos[SSD_MAX_DRAFT + 1], acc_tok[SSD_MAX_DRAFT + 1];
     int next_pos[SSD_MAX_DRAFT + 1], next_tok[SSD_MAX_DRAFT + 1];
 };
@@ -94,7 +101,7 @@ struct Dims {
     // most nodes one forward of this context can hold
     int max_nodes() const {
         const int tree = 2 * max_draft > max_draft + 1 ? 2 * max_draft : max_draft + 1;
-        return max_seqs * (tree + 1 > 3 ? tree + 1 : 3);           // a cache refresh takes three nodes
+        return max_seqs * (tree + 1 > 4 ? tree + 1 : 4);           // a cache refresh takes up to four nodes
     }
     // rows of the own-key / own-value buffers: every node starts on a 64-row boundary
     int vt_rows() const { return ((max_rows + 63) & ~63) + 64 * max_nodes(); }
@@ -152,6 +159,8 @@ struct Buffers {
     SeqState* state;     // [max_seqs]
     StepResult* result;  // [max_seqs]
     int* out_tok;        // [max_seqs, max_seq_len] device token output of ssd_generate
+    float* ref_conf;     // [max_seqs, max_seq_len] confidence per position at the sequence's last cache refresh
+    int* ref_arg;        // [max_seqs, max_seq_len] arg-max token per position at that refresh
     float* probe_logits; // [block, V] logits of a round's first forward (ssd_acceptance_limit)
     int* probe_rank;     // [SSD_MAX_DRAFT + 1]
     int lm_tiles;        // vocab tiles of the LM-head reduction
@@ -184,6 +193,7 @@ struct ssd_ctx {
     int fuse_boundary;   // ssd_generate: KV append + next block's draft in one forward
     int tree_mode;       // 0 = greedy chain (Section 3.2.3), 1 = mix-order tree (Section 5.2)
     int cross_block;     // ssd_generate: the last round of a block may reach into the next block (Section 3.2.2)
+    int spill_over;      // ssd_generate with the dual cache: the chain continues into the next block (Section 3.2.2)
     // HIP graphs of the forward's kernel sequence, one per launch shape.  Everything that changes
     // between forwards of one shape (tokens, prefix lengths, drafts, output pointers) lives in
     // device memory, so a shape's second forward is captured and later ones replay the graph.

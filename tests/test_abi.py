@@ -82,7 +82,7 @@ def test_config_validation_needs_no_gpu(lib):
     assert lib.ssd_destroy(None) == -1
     # the option setters reject a null context without touching the device
     for name in ("ssd_set_kernel_path", "ssd_set_boundary_fusion", "ssd_set_tree_mode", "ssd_set_graphs",
-                 "ssd_set_cross_block"):
+                 "ssd_set_cross_block", "ssd_set_spill_over"):
         assert getattr(lib, name)(None, 1) == -1, name
     assert lib.ssd_set_cache_mode(None, 1, 8) == -1
     assert lib.ssd_refresh_kv(None, 0, None, 0, 0, 0, 0, None) == -1

@@ -175,7 +175,16 @@ def test_dual_cache_with_periodic_refresh_bf16(shallow8b):
             out, st = eng.generate([prompt], 56, blk, 4)
             assert np.array_equal(out, base), (blk, R)
             assert st["kv_passes"] == s0["kv_passes"] and st["forwards"] <= s0["forwards"]
-            print(f"dual cache block {blk} refresh {R}: forwards {st['forwards']} (stepwise 56), refreshes {st['kv_passes']}")
+            # spill-over (Section 3.2.2): the chain continues into the next block; same tokens, no more forwards
+            eng.set_spill_over(1)
+            try:
+                out_s, st_s = eng.generate([prompt], 56, blk, 4)
+            finally:
+                eng.set_spill_over(0)
+            assert np.array_equal(out_s, base), ("spill-over", blk, R)
+            assert st_s["kv_passes"] == s0["kv_passes"] and st_s["forwards"] <= st["forwards"]
+            print(f"dual cache block {blk} refresh {R}: forwards {st['forwards']} (stepwise 56, with spill-over "
+                  f"{st_s['forwards']}), refreshes {st['kv_passes']}")
     finally:
         eng.set_cache_mode(0)
     plain, _ = eng.generate([prompt], 56, 8, 4)

@@ -42,7 +42,11 @@ def test_cfg2_full_depth():
     eng.set_cache_mode(1, 8)
     base_d, sd0 = eng.generate([prompt], 2 * B, B, 0)
     out_d, sd4 = eng.generate([prompt], 2 * B, B, N)
+    eng.set_spill_over(1)
+    out_s, sds = eng.generate([prompt], 2 * B, B, N)
+    eng.set_spill_over(0)
     eng.set_cache_mode(0)
+    assert np.array_equal(out_s, base_d) and sds["forwards"] <= sd4["forwards"], "spill-over with the dual cache"
     assert np.array_equal(out_d, base_d) and sd0["kv_passes"] == sd4["kv_passes"] == 2 * B // 8
     print("dual cache forwards", sd4["forwards"], "of", sd0["forwards"], flush=True)
     print("copying weights to the host for the oracle", flush=True)

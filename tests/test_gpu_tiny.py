@@ -383,6 +383,67 @@ def test_dual_cache_with_periodic_refresh(setup):
         eng.close()
 
 
+def test_spill_over_with_the_dual_cache(setup):
+    """Section 3.2.2's spill-over under the cache of Section 4.1 (ssd_set_spill_over): the chain continues into
+    the next block, drafts of unpredicted blocks come from the last refresh.  Tokens equal stepwise decoding on
+    the GPU bit for bit; forwards, refreshes and the acceptance histogram equal the oracle's ssd_dual_spill;
+    never more forwards than the in-block chain; zero attention reaches the closed form; two sequences."""
+    from paper_2510_04147_amd import binding
+    cfg, w, wg, _ = setup
+    eng = binding.SSD(cfg, wg, max_seqs=2, max_seq_len=256, block=32, max_draft=8, max_rows=2 * 9 * 32)
+    try:
+        for (P, gen, blk, R) in ((37, 40, 8, 8), (48, 64, 32, 8), (30, 40, 8, 11), (30, 43, 8, 0), (30, 24, 8, 1000),
+                                 (21, 40, 5, 3), (16, 48, 8, 16)):
+            prompt = synth.gen_prompt(cfg, 200 + P, P)
+            Re = R if R > 0 else blk
+            eng.set_cache_mode(1, R)
+            eng.set_spill_over(0)
+            base, s0 = eng.generate([prompt], gen, blk, 0)
+            want, _ = decode.stepwise_dual(w, cfg, prompt, gen, blk, Re)
+            same = list(base[0]) == want
+            for N in (1, 4, 8):
+                eng.set_spill_over(0)
+                inb, s1 = eng.generate([prompt], gen, blk, N)
+                eng.set_spill_over(1)
+                out, st = eng.generate([prompt], gen, blk, N)
+                step, ss = eng.generate([prompt], gen, blk, 0)           # stepwise decoding is not affected
+                assert np.array_equal(out, base) and np.array_equal(step, base) and ss["forwards"] == gen, (P, R, N)
+                assert st["tokens"] == gen and st["kv_passes"] == s0["kv_passes"]
+                assert st["forwards"] <= s1["forwards"], (P, R, N, st, s1)
+                if same:
+                    ro, so = decode.ssd_dual_spill(w, cfg, prompt, gen, blk, N, Re)
+                    assert st["forwards"] == so["forwards"], (P, R, N, st, so)
+                    assert st["accept_hist"][:N + 2] == so["accept_hist"][:N + 2], (P, R, N)
+                    print(f"P={P} block={blk} R={Re} N={N}: forwards {st['forwards']} (in-block chain {s1['forwards']})")
+        # two sequences at once, different prompt lengths and so different refresh moments
+        p0, p1 = synth.gen_prompt(cfg, 31, 50), synth.gen_prompt(cfg, 32, 23)
+        eng.set_cache_mode(1, 8)
+        eng.set_spill_over(1)
+        both, st = eng.generate([p0, p1], 40, 8, 4)
+        a, _ = eng.generate([p0], 40, 8, 0)
+        b, _ = eng.generate([p1], 40, 8, 0)
+        assert np.array_equal(both[0], a[0]) and np.array_equal(both[1], b[0]) and st["tokens"] == 80
+    finally:
+        eng.set_spill_over(0)
+        eng.set_cache_mode(0)
+        eng.close()
+    # zero attention: every draft verifies, also those read off the refresh; block boundaries cost nothing
+    w0 = {k: v for k, v in wg.items() if k != "layers"}
+    w0["layers"] = [dict(lw, wo=torch.zeros_like(lw["wo"])) for lw in wg["layers"]]
+    eng0 = binding.SSD(cfg, w0, max_seqs=1, max_seq_len=256, block=32, max_draft=8, max_rows=9 * 32)
+    try:
+        prompt = synth.gen_prompt(cfg, 5, 10)
+        for (N, R, blk, gen) in ((4, 8, 8, 48), (3, 8, 8, 40), (5, 12, 6, 48), (4, 8, 32, 64), (2, 5, 8, 43)):
+            eng0.set_cache_mode(1, R)
+            eng0.set_spill_over(1)
+            out, st = eng0.generate([prompt], gen, blk, N)
+            full, rem = divmod(gen, R)
+            want = full * (1 + math.ceil((R - 1) / (N + 1))) + ((1 + math.ceil((rem - 1) / (N + 1))) if rem else 0)
+            assert st["forwards"] == want and len(set(out[0].tolist())) == 1, (N, R, blk, gen, st)
+    finally:
+        eng0.close()
+
+
 def test_acceptance_limit_probe(setup):
     """Section 5.1 / Table 2 (ssd_acceptance_limit): rounds of N+1 stepwise steps, every decoded token
     ranked in the round's first logits.  Tokens equal stepwise decoding; where they also equal the

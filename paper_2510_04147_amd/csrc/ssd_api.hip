@@ -891,8 +891,9 @@ static int generate_dual(ssd_ctx* c, int n, const int32_t* const* prompts, const
         }
         // refreshes: the positions right behind the block, as far as decoding can get before the next refresh,
         // keep their predictions (the drafts of the blocks entered until then); they need logits, so they follow
-        // the decode groups directly
-        for (int i = 0; spill && i < n; ++i) {
+        // the decode groups directly.  (Also without spill-over: how a refresh is cut into segments fixes the
+        // summation order of its attention rows, and the switch must not change a single bit of the tokens.)
+        for (int i = 0; i < n; ++i) {
             if (!live_seq[i] || !refresh_now[i]) continue;
             const int S = prompt_len[i] + blk[i] * block, bl = block_len(blk[i]), T = prompt_len[i] + gen_len;
             const int from = S + bl, upto = std::min(T, from + ((R + block - 1) / block + 1) * block);

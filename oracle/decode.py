@@ -64,7 +64,7 @@ Readings where the paper is silent (all also applied by the HIP path):
     so the leaf node always has a position left to predict; with zero drafts the
     verification forward is a plain stepwise step (Algorithm 1's fallback);
   * next drafts are read off the last valid node's own outputs, no extra
-    forward (Section 3.2.4, "without duplicate context").
+    forward (Section 3.2.4: the verification pass already holds that node's outputs).
 """
 from __future__ import annotations
 

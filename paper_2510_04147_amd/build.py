@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssd_mi355x.so")
 MEASURE_LIB = os.path.join(HERE, "libssd_measure.so")      # measurement kernels only, not part of the product
-SOURCES = ["kernels_mfma.hip", "kernels_mfma_f32.hip", "ssd_api.hip", "kernels_plain.hip"]
+SOURCES = ["kernels_mfma.hip", "kernels_mfma_f32.hip", "gemm_f32_wn3.hip", "gemm_f32_wn2.hip", "gemm_f32_wn4.hip",
+           "gemm_swiglu_wn3.hip", "gemm_swiglu_wn4.hip", "gemm_lmhead_wn4.hip", "ssd_api.hip", "kernels_plain.hip"]
 MEASURE_SOURCES = ["measure.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -27,7 +28,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES + MEASURE_SOURCES))
     for lib, ob in ((LIB, objs[:len(SOURCES)]), (MEASURE_LIB, objs[len(SOURCES):])):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *ob, "-o", lib]

@@ -1,0 +1,8 @@
+// fp32 partial sums, 128-row n-blocks (the down projection): 24 chunks per k-slice at d_ffn 12288
+// (one instantiation unit of the MFMA GEMM template; see kernels_mfma.hip for the design)
+#include "gemm_mfma.h"
+
+bool gemm_f32_wn4(const GemmArgs& a) {
+    return launch_shape<4, 2, EPI_F32, 24>(a.nch, a.mt, a.X, a.Wp, a.out, a.M, a.N, a.K, a.split, a.split_stride, a.mask_id,
+                                         a.n_tiles_out, a.m_chunks, a.st);
+}

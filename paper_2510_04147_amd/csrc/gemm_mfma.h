@@ -472,8 +472,9 @@ static bool launch_one(const bf16_t* X, const uint4* Wp, void* out, int M, int N
     return true;
 }
 
-// Row tiles per pass: 1 (a stepwise forward of one block), 2, 5 (a 5-node tree) or 6;
-// other row counts round up (padding rows are zero and never stored).
+// Row tiles of 32 rows per pass: 1 (a stepwise forward of one block) to 6; other row counts round up
+// (padding rows are zero and never stored).  The rows of a pass share nothing but the weight fragments,
+// so a row's sums do not depend on the tile it is computed in.
 template <int WN, int WK, int R, int EPI, int NCH>
 static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
                       size_t split_stride, int mask_id, int n_tiles_out, int m_chunks,
@@ -493,6 +494,8 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
     switch (mt) {
         SSD_MT_CASE(1)
         SSD_MT_CASE(2)
+        SSD_MT_CASE(3)
+        SSD_MT_CASE(4)
         SSD_MT_CASE(5)
         SSD_MT_CASE(6)
     }
@@ -500,30 +503,33 @@ static bool launch_mt(int mt, const bf16_t* X, const uint4* Wp, void* out, int M
     return false;
 }
 
-// Chunk counts with a straight-line kernel; anything else takes the looped one (NCH = 0).
-template <int WN, int WK, int R, int EPI>
-static bool launch_nch(int nch, int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
-                       size_t split_stride, int mask_id, int n_tiles_out, int m_chunks,
-                       hipStream_t st) {
-#define SSD_NCH_CASE(v)                                                                                           \
-    case v:                                                                                                       \
-        return launch_mt<WN, WK, R, EPI, v>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id,      \
-                                         n_tiles_out, m_chunks, st);
-    if (EPI == EPI_F32) {
-        switch (nch) {
-            SSD_NCH_CASE(8)
-            SSD_NCH_CASE(16)
-            SSD_NCH_CASE(24)
-            SSD_NCH_CASE(32)
-            SSD_NCH_CASE(64)
-        }
-    } else {
-        switch (nch) { SSD_NCH_CASE(64) }
-    }
-#undef SSD_NCH_CASE
-    return launch_mt<WN, WK, R, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out,
-                                     m_chunks, st);
+// One chunk count per work-group shape runs as straight-line code (NCH = the 8B-class shape's chunk
+// count for that projection); every other chunk count takes the looped kernel (NCH = 0).
+template <int WN, int WK, int EPI, int NCH>
+static bool launch_shape(int nch, int mt, const bf16_t* X, const uint4* Wp, void* out, int M, int N, int K, int split,
+                         size_t split_stride, int mask_id, int n_tiles_out, int m_chunks, hipStream_t st) {
+    if (NCH > 0 && nch == NCH)
+        return launch_mt<WN, WK, 1, EPI, NCH>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out, m_chunks, st);
+    return launch_mt<WN, WK, 1, EPI, 0>(mt, X, Wp, out, M, N, K, split, split_stride, mask_id, n_tiles_out, m_chunks, st);
 }
+
+// the launchers of the work-group shapes, one translation unit each (they compile in parallel)
+struct GemmArgs {
+    int nch, mt;
+    const bf16_t* X;
+    const uint4* Wp;
+    void* out;
+    int M, N, K, split;
+    size_t split_stride;
+    int mask_id, n_tiles_out, m_chunks;
+    hipStream_t st;
+};
+bool gemm_f32_wn3(const GemmArgs& a);     // wide outputs (QKV): 96-row n-blocks
+bool gemm_f32_wn2(const GemmArgs& a);     // narrow outputs, short K (attention output): 64-row n-blocks
+bool gemm_f32_wn4(const GemmArgs& a);     // narrow outputs, long K (down) and everything else: 128-row n-blocks
+bool gemm_swiglu_wn3(const GemmArgs& a);
+bool gemm_swiglu_wn4(const GemmArgs& a);
+bool gemm_lmhead_wn4(const GemmArgs& a);
 
 // Split along K across work-groups: a function of the weight shape only.
 static int pick_split(int K, int kc, int want) {

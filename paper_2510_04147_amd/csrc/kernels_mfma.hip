@@ -60,28 +60,29 @@ bool launch_gemm_mfma(const ssd_ctx* c, int epi, const void* X, const Wt& W, voi
                       hipStream_t st) {
     if (!W.packed) return false;
     const int N = W.N, K = W.K;
-    constexpr int WN = 4, WK = 2, KC = WK * 32;
+    constexpr int WK = 2, KC = WK * 32;
     if (K % KC) return false;
-    // rows per pass: 32, 64 or 160 (a 5-node tree of 32-row blocks); forwards with more rows re-stream the
-    // weights once per pass, in passes of 160 or 192 rows, whichever needs fewer.  The rows of a pass share
-    // nothing but the weight fragments, so a row's sums do not depend on the choice.
-    int mt = M <= 32 ? 1 : M <= 64 ? 2 : 5;
-    if (M > 160 && (M + 191) / 192 < (M + 159) / 160) mt = 6;
+    // rows per pass: 32 ... 192 in steps of 32; forwards with more rows re-stream the weights once per pass,
+    // in passes of 160 or 192 rows, whichever needs fewer.  The rows of a pass share nothing but the weight
+    // fragments, so a row's sums do not depend on the choice.
+    int mt = (M + 31) / 32;
+    if (mt > 6) mt = (M + 191) / 192 < (M + 159) / 160 ? 6 : 5;
     const int rows = mt * 32, m_chunks = (M + rows - 1) / rows;
     const bf16_t* x = (const bf16_t*)X;
     const uint4* wp = (const uint4*)W.packed;
+    GemmArgs a{K / KC, mt, x, wp, out, M, N, K, 1, 0, -1, 0, m_chunks, st};
     if (epi == EPI_SWIGLU) {
         // W = [2F, d] packed with gate and up rows interleaved per 16 channels: N/32 tiles of 16
         // channels each, any number of them per work-group; 96-row n-blocks give the 8B shape
         // (768 tiles) exactly one work-group per CU
         *n_split = 1;
-        if ((N / 32) % 3 == 0)
-            return launch_nch<3, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, N, K, 1, 0, -1, 0, m_chunks, st);
-        return launch_nch<WN, WK, 1, EPI_SWIGLU>(K / KC, mt, x, wp, out, M, N, K, 1, 0, -1, 0, m_chunks, st);
+        return (N / 32) % 3 == 0 ? gemm_swiglu_wn3(a) : gemm_swiglu_wn4(a);
     }
     if (epi == EPI_LMHEAD) {
         *n_split = lm_tiles_mfma(N);
-        return launch_nch<WN, WK, 1, EPI_LMHEAD>(K / KC, mt, x, wp, out, M, N, K, 1, 0, c->dm.mask_id, N / 32, m_chunks, st);
+        a.mask_id = c->dm.mask_id;
+        a.n_tiles_out = N / 32;
+        return gemm_lmhead_wn4(a);
     }
     return launch_gemm_mfma_f32(c, x, wp, out, M, N, K, mt, m_chunks, n_split, st);
 }

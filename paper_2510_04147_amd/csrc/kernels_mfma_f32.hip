@@ -4,7 +4,7 @@
 
 bool launch_gemm_mfma_f32(const ssd_ctx* c, const bf16_t* x, const uint4* wp, void* out, int M, int N, int K, int mt,
                           int m_chunks, int* n_split, hipStream_t st) {
-    constexpr int WN = 4, WK = 2, KC = WK * 32;
+    constexpr int WK = 2, KC = WK * 32;
     const size_t stride = (size_t)c->dm.max_rows * (size_t)c->part_cols;
     // Work-group shape and split along K: functions of the weight shape alone, chosen so that the
     // grid comes close to one work-group per CU (256) with at least 16 K chunks each where the
@@ -26,7 +26,6 @@ bool launch_gemm_mfma_f32(const ssd_ctx* c, const bf16_t* x, const uint4* wp, vo
     const int split = pick_split(K, KC, want);
     *n_split = split;
     const int nch = K / split / KC;
-    if (wn == 3) return launch_nch<3, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
-    if (wn == 2) return launch_nch<2, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
-    return launch_nch<WN, WK, 1, EPI_F32>(nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st);
+    GemmArgs a{nch, mt, x, wp, out, M, N, K, split, stride, -1, 0, m_chunks, st};
+    return wn == 3 ? gemm_f32_wn3(a) : wn == 2 ? gemm_f32_wn2(a) : gemm_f32_wn4(a);
 }

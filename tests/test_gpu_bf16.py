@@ -36,7 +36,7 @@ def shallow8b():
     eng.close()
 
 
-@pytest.mark.parametrize("M", [160, 32, 45])
+@pytest.mark.parametrize("M", [160, 32, 45, 96, 128])
 def test_linear_steps_against_fp64_products(shallow8b, M):
     """Each GEMM kernel alone: bf16 operands, fp32 accumulation, against fp64 on the same operands."""
     from paper_2510_04147_amd import binding as B

@@ -244,6 +244,15 @@ def main():
             eng.generate(prompts, B, B, N)                       # warm
             toks_ssd, st_ssd = eng.generate(prompts, G, B, N)
             toks_step, st_step = eng.generate(prompts, G, B, 0)
+            GT_ = G * nseq
+            # shorter chains, for context: with random weights few drafts verify, so a shallower tree (fewer rows
+            # per forward, the GEMM's row tile follows in steps of 32) trades less than it costs
+            sweep = {}
+            for nd in range(1, N):
+                t_nd, st_nd = eng.generate(prompts, G, B, nd)
+                sweep[str(nd)] = dict(tokens_per_s=GT_ / (st_nd["total_ms"] / 1e3), forwards=st_nd["forwards"],
+                                      ms_per_forward=st_nd["decode_ms"] / st_nd["forwards"],
+                                      equals_stepwise=bool(np.array_equal(t_nd, toks_step)))
             eng.set_tree_mode(1)                                 # the mix-order tree (Section 5.2), for context
             toks_mix, st_mix = eng.generate(prompts, G, B, N)
             eng.set_tree_mode(0)
@@ -251,7 +260,7 @@ def main():
             toks_x, st_x = eng.generate(prompts, G, B, N)
             eng.set_cross_block(0)
             same = bool(np.array_equal(toks_ssd, toks_step) and np.array_equal(toks_mix, toks_step) and
-                        np.array_equal(toks_x, toks_step))
+                        np.array_equal(toks_x, toks_step) and all(v["equals_stepwise"] for v in sweep.values()))
             # the cache of the paper's experiments (Section 4.1): prefix + suffix, renewed by a forward over the
             # whole sequence every 8 decoded tokens; a different model function, so its own stepwise run
             eng.set_cache_mode(1, 8)
@@ -271,6 +280,7 @@ def main():
                 ssd_decode_ms_per_forward=st_ssd["decode_ms"] / st_ssd["forwards"],
                 stepwise_ms_per_forward=st_step["decode_ms"] / st_step["forwards"],
                 ssd_equals_stepwise=same, ssd_total_ms=st_ssd["total_ms"], stepwise_total_ms=st_step["total_ms"],
+                draft_depth_sweep=sweep,
                 mix_order_tokens_per_s=GT / (st_mix["total_ms"] / 1e3), mix_order_forwards=st_mix["forwards"],
                 mix_order_accept_hist=st_mix["accept_hist"][:N + 2],
                 cross_block_tokens_per_s=GT / (st_x["total_ms"] / 1e3), cross_block_forwards=st_x["forwards"],

@@ -144,7 +144,7 @@ int ssd_cached_len(ssd_ctx* ctx, int seq);
  * Errors: SSD_ERANGE (n > max_rows, pos0+n > max_seq_len, token id out of range). */
 int ssd_prefill_kv(ssd_ctx* ctx, int seq, const int32_t* tokens, int n, int pos0);
 
-/* Self-draft (Section 3.2.2, Eq. 4; Algorithm 1 line 4): a one-node forward for
+/* Self-draft (Section 3.2.2, Eq. 4; the self-draft step of Algorithm 1): a one-node forward for
  * each listed sequence on its current block.  Accepts the stepwise choice (most
  * confident masked position) and returns up to n_draft_next drafts, the other
  * masked positions by descending confidence, always one fewer than remain

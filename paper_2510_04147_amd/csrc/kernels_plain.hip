@@ -553,7 +553,7 @@ __global__ __launch_bounds__(64) void k_accept(const FwdHeader* __restrict__ fw,
     int my_dpos = lane <= SSD_MAX_DRAFT ? s->draft_pos[lane] : -1;
     int my_dtok = lane <= SSD_MAX_DRAFT ? s->draft_tok[lane] : -1;
     if (g.from_refresh) drafts_from_refresh(g.S, blen, my_dpos, my_dtok);
-    // a fresh block starts all masked with no drafts (Algorithm 1, line 3); its state is written here,
+    // a fresh block starts all masked with no drafts (Algorithm 1, start of a block); its state is written here,
     // at the end of the forward, so that a KV-append group of the same sequence in the same forward
     // still reads the finished block's tokens
     unsigned long long cur = g.fresh ? (blen >= 64 ? ~0ull : ((1ull << blen) - 1ull)) : s->masked;
